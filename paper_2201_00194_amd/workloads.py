@@ -1,0 +1,354 @@
+"""Seeded synthetic workloads: families of candidate programs and their cost models.
+
+This module only *draws inputs*.  It holds none of the scoring method's arithmetic
+(no traversal, no sums, no ranking) so that both the CPU oracle's tests and the
+HIP path's tests can take their inputs from it without sharing any of the method.
+
+The tuner the paper describes keeps one gradient-boosted-tree cost model per
+subgraph family (Section 4.2, Algorithm 1: one model initialised per family) and
+uses it to estimate every generated candidate of the family's subgraphs before the
+best `g` go on to measurement (Section 4.2; `g = min(64, B / #subgraphs)`).  The
+real candidates' feature vectors come out of a tensor compiler that is not
+available here, so each workload below is a synthetic stand-in with the structure
+such a tuning round has: a few to a few dozen families (the paper's Table 1 lists
+9-38 subgraphs per network), each with its own ensemble, its own candidate
+programs, a handful of statements per program, and 164 features per statement.
+
+Five recipes (`CONFIGS`) are provided.  Every recipe can be shrunk with `scale`
+(fewer programs) and `trees` (fewer trees) so that a slow CPU oracle can score the
+whole case; the distributions and the structure stay the same.
+
+Conventions fixed here (and relied on by both implementations' callers):
+
+* A model is a concatenation of trees.  Tree `t` owns nodes
+  `[tree_off[t], tree_off[t+1])`; node ids inside the arrays are LOCAL to the tree
+  and the root is local node 0.
+* `split_feature[n] < 0` marks a leaf whose output is `value[n]`.  Otherwise the
+  node is internal and a row goes LEFT iff `x[split_feature[n]] < threshold[n]`
+  (strict), else RIGHT.
+* "depth d" counts split levels: a full tree of depth d has 2^d - 1 internal nodes
+  and 2^d leaves, numbered in heap order (children of n are 2n+1, 2n+2).  Irregular
+  trees are numbered in breadth-first order; children ids exceed the parent's.
+* Features are row-major float32, one row per statement; program `p` owns rows
+  `[prog_off[p], prog_off[p+1])`.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+N_FEATURES = 164
+
+
+@dataclass
+class Model:
+    """One family's tree ensemble as flat host arrays (see module docstring)."""
+    n_features: int
+    tree_off: np.ndarray       # int32 [T+1]
+    split_feature: np.ndarray  # int32 [N]  (<0 => leaf)
+    threshold: np.ndarray      # float32 [N]
+    left: np.ndarray           # int32 [N]  local child id, -1 at leaves
+    right: np.ndarray          # int32 [N]
+    value: np.ndarray          # float32 [N] leaf output (0 at internal nodes)
+    bias: float = 0.0
+
+    @property
+    def n_trees(self) -> int:
+        return int(self.tree_off.shape[0] - 1)
+
+    @property
+    def n_nodes(self) -> int:
+        return int(self.split_feature.shape[0])
+
+
+@dataclass
+class Family:
+    model: Model
+    features: np.ndarray   # float32 [R, D] row-major
+    prog_off: np.ndarray   # int32 [P+1]
+    k: int
+
+    @property
+    def n_rows(self) -> int:
+        return int(self.features.shape[0])
+
+    @property
+    def n_programs(self) -> int:
+        return int(self.prog_off.shape[0] - 1)
+
+
+@dataclass
+class Case:
+    name: str
+    seed: int
+    families: List[Family] = field(default_factory=list)
+    notes: str = ""
+
+    @property
+    def n_rows(self) -> int:
+        return sum(f.n_rows for f in self.families)
+
+    @property
+    def n_programs(self) -> int:
+        return sum(f.n_programs for f in self.families)
+
+    @property
+    def feature_bytes(self) -> int:
+        return sum(f.features.nbytes for f in self.families)
+
+
+# --------------------------------------------------------------------------------------
+# features
+# --------------------------------------------------------------------------------------
+
+def draw_features(rng: np.random.Generator, n_rows: int, zero_frac: float,
+                  n_features: int = N_FEATURES,
+                  col_scale: Optional[np.ndarray] = None) -> np.ndarray:
+    """Rows of `n_features` float32: each entry is exactly 0 with probability
+    `zero_frac`, else uniform on [0,1).  With `col_scale` (float64 per column) every
+    column is multiplied in float64 and rounded to float32 once."""
+    out = np.empty((n_rows, n_features), dtype=np.float32)
+    step = max(1, (1 << 22) // n_features)          # ~16 MB blocks keep temporaries small
+    for lo in range(0, n_rows, step):
+        hi = min(n_rows, lo + step)
+        u = rng.random((hi - lo, n_features), dtype=np.float32)
+        z = rng.random((hi - lo, n_features), dtype=np.float32) < np.float32(zero_frac)
+        u[z] = 0.0
+        if col_scale is not None:
+            u = (u.astype(np.float64) * col_scale[None, :]).astype(np.float32)
+        out[lo:hi] = u
+    return out
+
+
+def draw_col_scale(rng: np.random.Generator, n_features: int = N_FEATURES) -> np.ndarray:
+    """Per-column scale 10^U(-3,3), float64."""
+    return np.power(10.0, rng.uniform(-3.0, 3.0, size=n_features))
+
+
+# --------------------------------------------------------------------------------------
+# trees
+# --------------------------------------------------------------------------------------
+
+def _tree_shape_full(depth: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """(is_leaf, left, right) of a full tree of `depth` split levels, heap order."""
+    n_int = (1 << depth) - 1
+    n = (1 << (depth + 1)) - 1
+    ids = np.arange(n, dtype=np.int32)
+    is_leaf = ids >= n_int
+    left = np.where(is_leaf, -1, 2 * ids + 1).astype(np.int32)
+    right = np.where(is_leaf, -1, 2 * ids + 2).astype(np.int32)
+    return is_leaf, left, right
+
+
+def _tree_shape_irregular(rng: np.random.Generator, max_depth: int,
+                          q: float) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Breadth-first numbered tree.  The root is always internal; every other node
+    above `max_depth` independently becomes a leaf with probability `q`; nodes at
+    `max_depth` are leaves."""
+    is_leaf_parts, left_parts, right_parts = [], [], []
+    level_leaf = np.zeros(1, dtype=bool)            # root internal
+    if max_depth == 0:
+        level_leaf[:] = True
+    next_id = 1
+    depth = 0
+    while True:
+        n_int = int((~level_leaf).sum())
+        l = np.full(level_leaf.shape[0], -1, dtype=np.int32)
+        r = np.full(level_leaf.shape[0], -1, dtype=np.int32)
+        child0 = next_id + 2 * np.arange(n_int, dtype=np.int32)
+        l[~level_leaf] = child0
+        r[~level_leaf] = child0 + 1
+        is_leaf_parts.append(level_leaf)
+        left_parts.append(l)
+        right_parts.append(r)
+        if n_int == 0:
+            break
+        next_id += 2 * n_int
+        depth += 1
+        if depth >= max_depth:
+            level_leaf = np.ones(2 * n_int, dtype=bool)
+        else:
+            level_leaf = rng.random(2 * n_int) < q
+    return (np.concatenate(is_leaf_parts), np.concatenate(left_parts),
+            np.concatenate(right_parts))
+
+
+def draw_model(rng: np.random.Generator, features: np.ndarray, n_trees: int, depth: int,
+               early_leaf_q: float = 0.0, leaf_sigma: float = 0.1,
+               bias: float = 0.0) -> Model:
+    """An ensemble over the columns of `features`.
+
+    Split features are uniform over the columns.  A node that splits on column j takes
+    as threshold the value X[r', j] of a row r' drawn uniformly from `features`, so the
+    threshold distribution follows the column's own (zeros and scale included).  Leaf
+    outputs are N(0, leaf_sigma) float32.  `early_leaf_q == 0` gives full trees of
+    `depth`; otherwise irregular trees of at most `depth`."""
+    n_rows, n_features = features.shape
+    shapes = []
+    if early_leaf_q <= 0.0:
+        shape = _tree_shape_full(depth)
+        shapes = [shape] * n_trees
+    else:
+        shapes = [_tree_shape_irregular(rng, depth, early_leaf_q) for _ in range(n_trees)]
+    sizes = np.array([s[0].shape[0] for s in shapes], dtype=np.int64)
+    tree_off = np.zeros(n_trees + 1, dtype=np.int32)
+    np.cumsum(sizes, out=tree_off[1:])
+    is_leaf = np.concatenate([s[0] for s in shapes]) if n_trees else np.zeros(0, bool)
+    left = np.concatenate([s[1] for s in shapes]) if n_trees else np.zeros(0, np.int32)
+    right = np.concatenate([s[2] for s in shapes]) if n_trees else np.zeros(0, np.int32)
+    n = is_leaf.shape[0]
+    feat = rng.integers(0, n_features, size=n, dtype=np.int32)
+    if n_rows > 0:
+        src_row = rng.integers(0, n_rows, size=n, dtype=np.int64)
+        thr = features[src_row, feat].astype(np.float32)
+    else:
+        thr = rng.random(n, dtype=np.float32)
+    val = (rng.standard_normal(n) * leaf_sigma).astype(np.float32)
+    split_feature = np.where(is_leaf, -1, feat).astype(np.int32)
+    threshold = np.where(is_leaf, np.float32(0), thr).astype(np.float32)
+    value = np.where(is_leaf, val, np.float32(0)).astype(np.float32)
+    return Model(n_features=n_features, tree_off=tree_off, split_feature=split_feature,
+                 threshold=threshold, left=left.astype(np.int32),
+                 right=right.astype(np.int32), value=value, bias=float(bias))
+
+
+# --------------------------------------------------------------------------------------
+# program structure
+# --------------------------------------------------------------------------------------
+
+def fixed_prog_off(n_programs: int, stmts: int) -> np.ndarray:
+    return (np.arange(n_programs + 1, dtype=np.int64) * stmts).astype(np.int32)
+
+
+def uniform_prog_off(rng: np.random.Generator, n_programs: int, lo: int, hi: int) -> np.ndarray:
+    s = rng.integers(lo, hi + 1, size=n_programs, dtype=np.int64)
+    off = np.zeros(n_programs + 1, dtype=np.int64)
+    np.cumsum(s, out=off[1:])
+    return off.astype(np.int32)
+
+
+def zipf_program_counts(n_families: int, largest: int, smallest: int, exponent: float) -> List[int]:
+    """Rank-size rule P_i = clamp(round(largest * i^-exponent), smallest, largest)."""
+    out = []
+    for i in range(1, n_families + 1):
+        p = int(round(largest * (i ** (-exponent))))
+        out.append(max(smallest, min(largest, p)))
+    return out
+
+
+# --------------------------------------------------------------------------------------
+# the five recipes
+# --------------------------------------------------------------------------------------
+
+@dataclass(frozen=True)
+class Recipe:
+    name: str
+    families: int
+    trees: int
+    depth: int
+    early_leaf_q: float
+    zero_frac: float
+    k: int
+    description: str
+
+
+CONFIGS: Sequence[Recipe] = (
+    Recipe("cfg0_single_small", 1, 100, 6, 0.0, 0.30, 64,
+           "1 family, 100 full trees depth 6, 4096 programs x 8 statements"),
+    Recipe("cfg1_eight_families", 8, 300, 8, 0.0, 0.30, 128,
+           "8 families, 300 full trees depth 8 each, 10000 programs x 16 statements each"),
+    Recipe("cfg2_large_population", 1, 500, 10, 0.0, 0.30, 1024,
+           "1 family, 500 full trees depth 10, 262144 programs x 8 statements"),
+    Recipe("cfg3_powerlaw_families", 30, 200, 8, 0.2, 0.50, 64,
+           "30 families, Zipf(1.2) program counts 65536..256, 1..64 statements, "
+           "200 irregular trees of depth <= 8 (early leaf 0.2)"),
+    Recipe("cfg4_deep_irregular", 64, 400, 12, 0.3, 0.30, 256,
+           "64 families, 400 irregular trees of depth <= 12 (early leaf 0.3), 2M rows, "
+           "1..32 statements, log-uniform column scales"),
+)
+
+
+def _scaled(n: int, scale: float, floor: int = 1) -> int:
+    return max(floor, int(round(n * scale)))
+
+
+def make_case(cfg: int, seed: int = 0, scale: float = 1.0, trees: Optional[int] = None,
+              k: Optional[int] = None) -> Case:
+    """Build workload `cfg` (0..4).
+
+    `scale` multiplies program counts (cfg 4: the total row count), `trees` overrides
+    the number of trees per family, `k` overrides the cut.  scale=1 and no overrides
+    give the full-size workload.  The generator stream is `default_rng([seed, cfg])`.
+    """
+    rc = CONFIGS[cfg]
+    rng = np.random.default_rng([seed, cfg])
+    n_trees = rc.trees if trees is None else int(trees)
+    kk = rc.k if k is None else int(k)
+    case = Case(name=rc.name, seed=seed,
+                notes=f"{rc.description}; scale={scale}, trees={n_trees}, k={kk}")
+
+    if cfg in (0, 1, 2):
+        per_family = {0: (4096, 8), 1: (10000, 16), 2: (262144, 8)}[cfg]
+        n_prog = _scaled(per_family[0], scale)
+        for _ in range(rc.families):
+            off = fixed_prog_off(n_prog, per_family[1])
+            X = draw_features(rng, int(off[-1]), rc.zero_frac)
+            m = draw_model(rng, X, n_trees, rc.depth)
+            case.families.append(Family(m, X, off, kk))
+        return case
+
+    if cfg == 3:
+        counts = zipf_program_counts(rc.families, 65536, 256, 1.2)
+        counts = [_scaled(c, scale, floor=4) for c in counts]
+        order = rng.permutation(rc.families)
+        for i in order:
+            off = uniform_prog_off(rng, counts[int(i)], 1, 64)
+            X = draw_features(rng, int(off[-1]), rc.zero_frac)
+            m = draw_model(rng, X, n_trees, rc.depth, early_leaf_q=rc.early_leaf_q)
+            case.families.append(Family(m, X, off, kk))
+        return case
+
+    if cfg == 4:
+        total_rows = _scaled(2_000_000, scale, floor=rc.families * 8)
+        # programs of 1..32 statements until the row budget is met (last one truncated)
+        est = int(total_rows / 16.5 * 1.2) + 64
+        s = rng.integers(1, 33, size=est, dtype=np.int64)
+        while s.sum() < total_rows:
+            s = np.concatenate([s, rng.integers(1, 33, size=est, dtype=np.int64)])
+        c = np.cumsum(s)
+        n_prog = int(np.searchsorted(c, total_rows, side="left")) + 1
+        s = s[:n_prog].copy()
+        s[-1] -= int(c[n_prog - 1] - total_rows)
+        fam_of = rng.integers(0, rc.families, size=n_prog)
+        for f in range(rc.families):
+            sf = s[fam_of == f]
+            off = np.zeros(sf.shape[0] + 1, dtype=np.int64)
+            np.cumsum(sf, out=off[1:])
+            scale_cols = draw_col_scale(rng)
+            X = draw_features(rng, int(off[-1]), rc.zero_frac, col_scale=scale_cols)
+            m = draw_model(rng, X, n_trees, rc.depth, early_leaf_q=rc.early_leaf_q)
+            case.families.append(Family(m, X, off.astype(np.int32), kk))
+        return case
+
+    raise ValueError(f"unknown config {cfg}")
+
+
+def make_small_family(seed: int, n_programs: int, stmts: Tuple[int, int], n_trees: int,
+                      depth: int, early_leaf_q: float = 0.0, zero_frac: float = 0.3,
+                      n_features: int = N_FEATURES, k: int = 16, bias: float = 0.0,
+                      dyadic_leaves: bool = False) -> Family:
+    """A free-form family for tests.  With `dyadic_leaves` every leaf output is an
+    integer multiple of 1/1024 with magnitude < 1, so any fp32 sum of fewer than 2^13
+    of them is exact whatever the order of additions."""
+    rng = np.random.default_rng([seed, 977])
+    lo, hi = stmts
+    off = uniform_prog_off(rng, n_programs, lo, hi) if hi > lo else fixed_prog_off(n_programs, lo)
+    X = draw_features(rng, int(off[-1]), zero_frac, n_features=n_features)
+    m = draw_model(rng, X, n_trees, depth, early_leaf_q=early_leaf_q, bias=bias)
+    if dyadic_leaves:
+        leaf = m.split_feature < 0
+        q = rng.integers(-1023, 1024, size=m.n_nodes).astype(np.float32) / np.float32(1024)
+        m.value = np.where(leaf, q, np.float32(0)).astype(np.float32)
+    return Family(m, X, off, k)
