@@ -1,0 +1,160 @@
+"""Benchmark of the scoring hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C] [--seed S]
+
+A step is one pass of the whole path over one batch: fs_score_families (tree traversal,
+per-row ensemble sum, per-program segmented sum) for every family of the workload, then
+fs_topk for every family.  Inputs (column-blocked features, CSR offsets, models) are
+resident in HBM before the timed region.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload 0..4")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debug only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus %d is not supported "
+              "(no collectives, no sharding in this library)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2201_00194_amd import api, workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    t0 = time.time()
+    case = W.make_case(args.config, seed=args.seed, scale=args.scale)
+    gen_s = time.time() - t0
+    devs = [api.DeviceFamily(f, layout=api.FS_COLBLOCK64) for f in case.families]
+    fams = api.PreparedFamilies([d.family() for d in devs])
+    reqs = api.PreparedTopk([d.topk_request() for d in devs])
+    n_rows, n_prog = case.n_rows, case.n_programs
+    torch.cuda.synchronize()
+
+    def step():
+        api.fs_score_families(fams)
+        api.fs_topk(reqs)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    api.fs_profile_begin(4 * args.steps + 8)
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    w0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - w0) * 1e3
+    prof = api.fs_profile_end()
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = max(ev_ms, 0.0) / args.steps
+    rows_per_s = n_rows / (ms_per_step * 1e-3)
+
+    # ---- roofline of the dominant kernel (traversal) ------------------------------------------
+    # Algorithmic bytes per launch: every feature once (n_features * 4 B per row), one fp32 row
+    # score written per row, each family's model read once.
+    trav_ms, trav_n = prof["traverse"]
+    model_bytes = sum(16 * f.model.n_nodes + 4 * (f.model.n_trees + 1) for f in case.families)
+    alg_bytes = sum(f.n_rows * (f.model.n_features * 4 + 4) for f in case.families) + model_bytes
+    trav_avg_ms = trav_ms / max(1, trav_n)
+    achieved = alg_bytes / (trav_avg_ms * 1e-3) / 1e9 if trav_avg_ms > 0 else 0.0
+    visits = 0.0
+    roofline = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                "kernel": "traverse", "kernel_avg_ms": round(trav_avg_ms, 5),
+                "algorithmic_bytes_per_launch": int(alg_bytes)}
+
+    out = {
+        "metric": "statement-rows scored/sec + achieved HBM GB/s (% of peak); per-family top-k us",
+        "value": round(rows_per_s, 1),
+        "unit": "rows/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "configs[%d] %s" % (args.config, case.name), "seed": args.seed,
+                   "scale": args.scale, "families": len(case.families), "rows": n_rows,
+                   "programs": n_prog, "feature_layout": "colblock64",
+                   "feature_bytes": int(case.feature_bytes)},
+        "roofline": roofline,
+        "kernels_ms_per_step": {k: round(v[0] / max(1, args.steps), 5) for k, v in prof.items()},
+        "topk_us_per_family": round(prof["topk"][0] / max(1, prof["topk"][1]) * 1e3
+                                    / max(1, len(case.families)), 3),
+        "host_wall_ms_per_step": round(wall_ms / args.steps, 5),
+        "workload_gen_s": round(gen_s, 2),
+    }
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample -----------------------------
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        O.build()
+        threads = min(16, os.cpu_count() or 1)
+        budget_visits = 1.5e9      # roughly 20-30 core-seconds of the oracle
+        sample_rows = 0
+        t_cpu = 0.0
+        desc = []
+        for fi, f in enumerate(case.families):
+            if sample_rows and t_cpu > 20.0:
+                break
+            per_row = max(1.0, float(f.model.n_trees) * max(1, int(np.log2(max(2, f.model.n_nodes / max(1, f.model.n_trees))))))
+            want_rows = int(budget_visits / per_row / max(1, min(len(case.families), 4)))
+            p_end = int(np.searchsorted(f.prog_off, want_rows, side="right")) - 1
+            p_end = max(1, min(f.n_programs, p_end))
+            sub_off = f.prog_off[: p_end + 1]
+            rows = int(sub_off[-1])
+            if rows == 0:
+                continue
+            c0 = time.perf_counter()
+            ps = O.score_programs(f.model, f.features[:rows], sub_off, threads=threads)
+            O.topk(ps, min(f.k, p_end))
+            t_cpu += time.perf_counter() - c0
+            sample_rows += rows
+            desc.append("family %d programs [0,%d) = %d rows" % (fi, p_end, rows))
+            if len(desc) >= 4:
+                break
+        out["cpu_baseline"] = {
+            "value": round(sample_rows / t_cpu, 1) if t_cpu > 0 else None, "unit": "rows/s",
+            "cores": threads, "kind": "oracle",
+            "sample": "; ".join(desc) + "; %.2f s wall" % t_cpu}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,195 @@
+/*
+ * familyseer.h -- C ABI of the MI355X (gfx950) family cost-model scoring library.
+ *
+ * The auto-tuner of the paper keeps one gradient-boosted-tree cost model per subgraph
+ * family (Section 4.2; Algorithm 1 initialises a model C[f] for every family f), lets
+ * that model estimate every generated candidate program of the family's subgraphs
+ * (Section 4.2, the tune step; Section 2 "Building the Cost Model"), and sends only the
+ * best g candidates on to measurement (Section 3.2 "select the top-k"; Algorithm 1,
+ * g = min(64, B / #subgraphs), g*p in the foresee step).  This library is that
+ * estimate-then-cut step for many families at once:
+ *
+ *   fs_score_families   every family's model scores its own candidates:
+ *                       tree traversal per (statement row, tree), per-row sum over the
+ *                       ensemble, per-program sum over the program's statement rows
+ *   fs_topk             per family, the k programs with the largest score
+ *
+ * Conventions (the paper leaves them open; both this library and its test oracle fix
+ * them the same way):
+ *   - larger score = better candidate; callers holding latencies negate them;
+ *   - at an internal node a row goes LEFT iff x[split_feature] < threshold (strict),
+ *     otherwise RIGHT; a NaN feature therefore goes right; no missing-value rule;
+ *   - row_score[r]  = bias + sum of reached leaf values, fp32, trees in ascending order;
+ *   - prog_score[p] = sum of its rows' scores, fp32, rows in ascending order, from +0;
+ *     both sums are plain sequential additions (no FMA, no reassociation), so results
+ *     are reproducible bit for bit;
+ *   - top-k order: score descending, then program index ascending; -0 ties with +0;
+ *     NaN scores order after every number.
+ *
+ * All functions return FS_OK (0) or a negative error code and never throw, abort or
+ * print.  After an error, fs_last_error() gives a message for the calling thread.
+ * "HOST" / "DEVICE" on a pointer says which memory it must point to.  Device pointers
+ * must belong to the device that is current when the call is made.  Descriptor arrays
+ * (fs_family[], fs_topk_req[]) are HOST memory and are only read during the call.
+ * Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ * and the call returns without waiting for it.
+ */
+#ifndef FAMILYSEER_H
+#define FAMILYSEER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    FS_OK = 0,
+    FS_EINVAL = -1,       /* bad argument (NULL pointer, negative size, malformed model, ...) */
+    FS_ENOMEM = -2,       /* host or device allocation failed                               */
+    FS_EDEVICE = -3,      /* a HIP call failed; fs_last_error() holds the HIP message       */
+    FS_EUNSUPPORTED = -4  /* valid request outside the implemented limits                   */
+};
+
+/* Feature matrix layouts. */
+enum {
+    FS_ROWMAJOR = 0,   /* x[r][j] at r*n_features + j                                        */
+    FS_COLBLOCK64 = 1  /* tiles of 64 rows, feature-major inside a tile:
+                          x[r][j] at (r/64)*n_features*64 + j*64 + (r%64);
+                          the last tile is padded to 64 rows (padding content is ignored);
+                          the buffer holds ceil(n_rows/64)*n_features*64 floats            */
+};
+
+/* Limits. */
+#define FS_MAX_FEATURES 4096     /* n_features per model                                    */
+#define FS_MAX_TREE_NODES 65535  /* nodes in one tree (leaf ids fit uint16_t)               */
+#define FS_MAX_TOPK 16384        /* k per request                                           */
+
+/* Message for the last error on this thread; static storage, never NULL. */
+const char *fs_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int fs_version(void);
+
+/* ---- models: one per family (Section 4.2: an individual cost model per family) -------- */
+
+typedef struct fs_model fs_model; /* opaque, owned by the library */
+
+/*
+ * Build a device-resident ensemble from HOST arrays (copied; the caller may free them
+ * on return).  Trees are concatenated: tree t owns nodes [tree_off[t], tree_off[t+1]),
+ * tree_off[0] = 0; node ids in `left`/`right` are LOCAL to the tree and the root is
+ * local node 0.  split_feature[n] < 0 marks a leaf whose output is value[n] (its
+ * threshold/left/right are ignored); otherwise 0 <= split_feature[n] < n_features and
+ * the node sends a row left iff x[split_feature[n]] < threshold[n].  Child ids must be
+ * greater than the parent's id and inside the tree (this rules out cycles); every tree
+ * needs at least one node and at most FS_MAX_TREE_NODES.  n_trees may be 0 (every row
+ * then scores `bias`).  `bias` is added once per row.
+ * Errors: FS_EINVAL for NULL/negative/malformed input, FS_ENOMEM, FS_EDEVICE.
+ * Synchronises with the device (plain hipMemcpy) before returning.
+ */
+int fs_model_create(fs_model **out, int32_t n_features, int32_t n_trees,
+                    const int32_t *tree_off /* HOST, n_trees+1 */,
+                    const int32_t *split_feature /* HOST, tree_off[n_trees] */,
+                    const float *threshold /* HOST */, const int32_t *left /* HOST */,
+                    const int32_t *right /* HOST */, const float *value /* HOST */,
+                    float bias);
+
+/* Free a model.  NULL is allowed.  The caller must make sure no enqueued work still
+ * uses it (synchronise the streams first). */
+void fs_model_destroy(fs_model *model);
+
+/* ---- scoring -------------------------------------------------------------------------- */
+
+/* One family: its model and its own candidates (Section 4.2: the family model estimates
+ * the candidates generated for the family's subgraph). */
+typedef struct fs_family {
+    const fs_model *model;  /* this family's ensemble                                       */
+    const float *features;  /* DEVICE, read-only, layout per `layout`; 16-byte aligned      */
+    int32_t layout;         /* FS_ROWMAJOR or FS_COLBLOCK64                                 */
+    int64_t n_rows;         /* statement rows, >= 0, < 2^31                                 */
+    const int32_t *prog_off; /* DEVICE, n_programs+1 entries: program p owns rows
+                                [prog_off[p], prog_off[p+1]); prog_off[0] = 0,
+                                non-decreasing, prog_off[n_programs] = n_rows.  The content
+                                is NOT validated on the device: a malformed array gives
+                                undefined results (but reads stay inside n_rows).           */
+    int32_t n_programs;     /* >= 0                                                         */
+    float *prog_score;      /* DEVICE out, n_programs floats                                */
+    float *row_score;       /* DEVICE out, n_rows floats, or NULL (library scratch is used) */
+    uint16_t *leaf_idx;     /* DEVICE out, n_rows*n_trees, row-major [row][tree]: the local
+                               id of the leaf reached; or NULL.  Verification aid: it adds
+                               2*n_trees bytes of writes per row.                           */
+} fs_family;
+
+/*
+ * Score all families in one batched submission (a fixed, small number of kernel
+ * launches whatever n_families is).  Families are independent; buffers of different
+ * families must not overlap.  Empty families (n_rows == 0 or n_programs == 0) are
+ * allowed.  Errors are detected on the host before anything is enqueued: FS_EINVAL
+ * (NULL pointers, negative sizes, unknown layout, misaligned features), FS_ENOMEM /
+ * FS_EDEVICE (scratch growth, launch failure).
+ * When a family passes row_score == NULL the library uses its own scratch buffer, which
+ * is shared by all calls on the device: such calls must not overlap in time on
+ * different streams.
+ */
+int fs_score_families(int32_t n_families, const fs_family *fams /* HOST */, void *stream);
+
+/* ---- top-k ---------------------------------------------------------------------------- */
+
+typedef struct fs_topk_req {
+    const float *score;  /* DEVICE in, n floats                                             */
+    int32_t n;           /* >= 0                                                            */
+    int32_t k;           /* 0 <= k <= FS_MAX_TOPK                                           */
+    int32_t *out_idx;    /* DEVICE out, k entries: indices into score, best first; entries
+                            past min(k,n) are -1                                            */
+    float *out_score;    /* DEVICE out, k entries, or NULL: the selected scores; entries
+                            past min(k,n) are -infinity                                     */
+} fs_topk_req;
+
+/*
+ * For every request, the k entries with the largest score, ordered by (score descending,
+ * index ascending) (Section 3.2: candidates are sorted by the model's estimate and the
+ * top k are kept; Algorithm 1: k = g, or g*p in the foresee step).  One batched
+ * submission for all requests.  Errors: FS_EINVAL, FS_EUNSUPPORTED (k > FS_MAX_TOPK),
+ * FS_ENOMEM, FS_EDEVICE.  Uses library scratch shared by all calls on the device: calls
+ * must not overlap in time on different streams.
+ */
+int fs_topk(int32_t n_requests, const fs_topk_req *reqs /* HOST */, void *stream);
+
+/* ---- layout helper -------------------------------------------------------------------- */
+
+/*
+ * Re-tile a row-major feature matrix (DEVICE, n_rows x n_features floats) into
+ * FS_COLBLOCK64 (DEVICE out, ceil(n_rows/64)*n_features*64 floats; padding rows are
+ * written as 0).  in and out must not overlap.  Not part of the scoring path proper:
+ * a producer that can emit FS_COLBLOCK64 directly never needs it.
+ */
+int fs_pack_colblock64(const float *rowmajor /* DEVICE */, int64_t n_rows, int32_t n_features,
+                       float *out /* DEVICE */, void *stream);
+
+/* Number of floats an FS_COLBLOCK64 buffer needs. */
+int64_t fs_colblock64_floats(int64_t n_rows, int32_t n_features);
+
+/* ---- per-kernel timing (measurement aid) ----------------------------------------------------- */
+
+/* Kernel classes reported by fs_profile_end. */
+enum { FS_KERNEL_TRAVERSE = 0, FS_KERNEL_SEGSUM = 1, FS_KERNEL_TOPK = 2, FS_KERNEL_PACK = 3,
+       FS_KERNEL_CLASSES = 4 };
+
+/*
+ * Between fs_profile_begin and fs_profile_end the library brackets every kernel group it
+ * launches with a pair of HIP events on the caller's stream (at most max_records groups;
+ * later ones go untimed).  fs_profile_end waits for the recorded events and adds up, per
+ * kernel class, the elapsed milliseconds (HOST out, FS_KERNEL_CLASSES doubles) and the
+ * number of timed groups (HOST out, FS_KERNEL_CLASSES ints; either may be NULL).
+ * The sections are the tuner's estimate step (traverse + segmented sum) and cut step
+ * (top-k) of Section 4.2.  Process-wide switch; not meant for concurrent use.
+ */
+int fs_profile_begin(int32_t max_records);
+int fs_profile_end(double *ms_by_kernel /* HOST */, int32_t *launches_by_kernel /* HOST */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FAMILYSEER_H */

@@ -1,0 +1,274 @@
+"""Thin ctypes binding of `libfamilyseer.so` (see include/familyseer.h).
+
+Only argument marshalling lives here: every step of scoring and of the top-k cut runs
+in the library's HIP kernels.  PyTorch supplies device memory and the current stream.
+The functions carry the names of the C entry points they call.  There is no CPU
+fallback: if the library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfamilyseer.so")
+
+FS_OK, FS_EINVAL, FS_ENOMEM, FS_EDEVICE, FS_EUNSUPPORTED = 0, -1, -2, -3, -4
+FS_ROWMAJOR, FS_COLBLOCK64 = 0, 1
+FS_MAX_TOPK = 16384
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first (python -m paper_2201_00194_amd.build); "
+        "there is no fallback path")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+
+class FsError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"familyseer error {code}: {message}")
+        self.code = code
+
+
+class _FsFamily(ctypes.Structure):
+    _fields_ = [("model", ctypes.c_void_p), ("features", ctypes.c_void_p),
+                ("layout", ctypes.c_int32), ("n_rows", ctypes.c_int64),
+                ("prog_off", ctypes.c_void_p), ("n_programs", ctypes.c_int32),
+                ("prog_score", ctypes.c_void_p), ("row_score", ctypes.c_void_p),
+                ("leaf_idx", ctypes.c_void_p)]
+
+
+class _FsTopkReq(ctypes.Structure):
+    _fields_ = [("score", ctypes.c_void_p), ("n", ctypes.c_int32), ("k", ctypes.c_int32),
+                ("out_idx", ctypes.c_void_p), ("out_score", ctypes.c_void_p)]
+
+
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_f32p = ctypes.POINTER(ctypes.c_float)
+_lib.fs_last_error.restype = ctypes.c_char_p
+_lib.fs_last_error.argtypes = []
+_lib.fs_version.restype = ctypes.c_int
+_lib.fs_version.argtypes = []
+_lib.fs_model_create.restype = ctypes.c_int
+_lib.fs_model_create.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32, ctypes.c_int32,
+                                 _i32p, _i32p, _f32p, _i32p, _i32p, _f32p, ctypes.c_float]
+_lib.fs_model_destroy.restype = None
+_lib.fs_model_destroy.argtypes = [ctypes.c_void_p]
+_lib.fs_score_families.restype = ctypes.c_int
+_lib.fs_score_families.argtypes = [ctypes.c_int32, ctypes.POINTER(_FsFamily), ctypes.c_void_p]
+_lib.fs_topk.restype = ctypes.c_int
+_lib.fs_topk.argtypes = [ctypes.c_int32, ctypes.POINTER(_FsTopkReq), ctypes.c_void_p]
+_lib.fs_pack_colblock64.restype = ctypes.c_int
+_lib.fs_pack_colblock64.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
+                                    ctypes.c_void_p, ctypes.c_void_p]
+_lib.fs_colblock64_floats.restype = ctypes.c_int64
+_lib.fs_colblock64_floats.argtypes = [ctypes.c_int64, ctypes.c_int32]
+
+
+_lib.fs_profile_begin.restype = ctypes.c_int
+_lib.fs_profile_begin.argtypes = [ctypes.c_int32]
+_lib.fs_profile_end.restype = ctypes.c_int
+_lib.fs_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), _i32p]
+KERNEL_CLASSES = ("traverse", "segsum", "topk", "pack")
+
+
+def _check(rc: int) -> None:
+    if rc != FS_OK:
+        raise FsError(rc, _lib.fs_last_error().decode("utf-8", "replace"))
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def fs_version() -> int:
+    return int(_lib.fs_version())
+
+
+def fs_last_error() -> str:
+    return _lib.fs_last_error().decode("utf-8", "replace")
+
+
+class fs_model:
+    """Owner of one `fs_model*` (one family's ensemble, device resident)."""
+
+    def __init__(self, n_features: int, tree_off, split_feature, threshold, left, right, value,
+                 bias: float = 0.0):
+        to = np.ascontiguousarray(tree_off, dtype=np.int32)
+        sf = np.ascontiguousarray(split_feature, dtype=np.int32)
+        th = np.ascontiguousarray(threshold, dtype=np.float32)
+        le = np.ascontiguousarray(left, dtype=np.int32)
+        ri = np.ascontiguousarray(right, dtype=np.int32)
+        va = np.ascontiguousarray(value, dtype=np.float32)
+        n_trees = int(to.shape[0]) - 1
+        handle = ctypes.c_void_p()
+        rc = _lib.fs_model_create(
+            ctypes.byref(handle), int(n_features), n_trees,
+            to.ctypes.data_as(_i32p), sf.ctypes.data_as(_i32p), th.ctypes.data_as(_f32p),
+            le.ctypes.data_as(_i32p), ri.ctypes.data_as(_i32p), va.ctypes.data_as(_f32p),
+            ctypes.c_float(bias))
+        _check(rc)
+        self._h = handle
+        self.n_features = int(n_features)
+        self.n_trees = n_trees
+
+    @classmethod
+    def from_arrays(cls, m) -> "fs_model":
+        """From any object with the fields of `workloads.Model`."""
+        return cls(m.n_features, m.tree_off, m.split_feature, m.threshold, m.left, m.right,
+                   m.value, m.bias)
+
+    def destroy(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h:
+            _lib.fs_model_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+class Family:
+    """Argument bundle for one `fs_family` entry; tensors live on the device."""
+
+    def __init__(self, model: fs_model, features: torch.Tensor, layout: int, n_rows: int,
+                 prog_off: torch.Tensor, prog_score: torch.Tensor,
+                 row_score: Optional[torch.Tensor] = None,
+                 leaf_idx: Optional[torch.Tensor] = None):
+        self.model, self.features, self.layout, self.n_rows = model, features, layout, int(n_rows)
+        self.prog_off, self.prog_score = prog_off, prog_score
+        self.row_score, self.leaf_idx = row_score, leaf_idx
+        self.n_programs = int(prog_off.shape[0]) - 1 if prog_off is not None else 0
+
+
+def _family_array(fams: Sequence[Family]):
+    arr = (_FsFamily * max(1, len(fams)))()
+    for i, f in enumerate(fams):
+        arr[i].model = f.model._h if f.model is not None else None
+        arr[i].features = _ptr(f.features)
+        arr[i].layout = f.layout
+        arr[i].n_rows = f.n_rows
+        arr[i].prog_off = _ptr(f.prog_off)
+        arr[i].n_programs = f.n_programs
+        arr[i].prog_score = _ptr(f.prog_score)
+        arr[i].row_score = _ptr(f.row_score)
+        arr[i].leaf_idx = _ptr(f.leaf_idx)
+    return arr
+
+
+class PreparedFamilies:
+    """A family array marshalled once, for callers that submit the same set repeatedly."""
+
+    def __init__(self, fams: Sequence[Family]):
+        self.fams = list(fams)
+        self.arr = _family_array(self.fams)
+        self.n = len(self.fams)
+
+
+def fs_score_families(fams, stream: Optional[torch.cuda.Stream] = None) -> None:
+    if not isinstance(fams, PreparedFamilies):
+        fams = PreparedFamilies(fams)
+    _check(_lib.fs_score_families(fams.n, fams.arr, _stream_ptr(stream)))
+
+
+class TopkRequest:
+    def __init__(self, score: Optional[torch.Tensor], n: int, k: int, out_idx: torch.Tensor,
+                 out_score: Optional[torch.Tensor] = None):
+        self.score, self.n, self.k, self.out_idx, self.out_score = score, int(n), int(k), out_idx, out_score
+
+
+class PreparedTopk:
+    def __init__(self, reqs: Sequence[TopkRequest]):
+        self.reqs = list(reqs)
+        self.n = len(self.reqs)
+        self.arr = (_FsTopkReq * max(1, self.n))()
+        for i, r in enumerate(self.reqs):
+            self.arr[i].score = _ptr(r.score)
+            self.arr[i].n = r.n
+            self.arr[i].k = r.k
+            self.arr[i].out_idx = _ptr(r.out_idx)
+            self.arr[i].out_score = _ptr(r.out_score)
+
+
+def fs_topk(reqs, stream: Optional[torch.cuda.Stream] = None) -> None:
+    if not isinstance(reqs, PreparedTopk):
+        reqs = PreparedTopk(reqs)
+    _check(_lib.fs_topk(reqs.n, reqs.arr, _stream_ptr(stream)))
+
+
+def fs_colblock64_floats(n_rows: int, n_features: int) -> int:
+    return int(_lib.fs_colblock64_floats(int(n_rows), int(n_features)))
+
+
+def fs_pack_colblock64(rowmajor: torch.Tensor, n_rows: int, n_features: int,
+                       out: Optional[torch.Tensor] = None,
+                       stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty(fs_colblock64_floats(n_rows, n_features), dtype=torch.float32,
+                          device=rowmajor.device)
+    _check(_lib.fs_pack_colblock64(_ptr(rowmajor), int(n_rows), int(n_features), _ptr(out),
+                                   _stream_ptr(stream)))
+    return out
+
+
+def fs_profile_begin(max_records: int) -> None:
+    _check(_lib.fs_profile_begin(int(max_records)))
+
+
+def fs_profile_end() -> dict:
+    """{kernel class: (total ms, timed launches)}"""
+    ms = (ctypes.c_double * 4)()
+    cnt = (ctypes.c_int32 * 4)()
+    _check(_lib.fs_profile_end(ms, cnt))
+    return {name: (float(ms[i]), int(cnt[i])) for i, name in enumerate(KERNEL_CLASSES)}
+
+
+# ---- conveniences for tests and the benchmark (allocation + marshalling only) ---------------
+
+class DeviceFamily:
+    """Uploads one `workloads.Family` and allocates its outputs."""
+
+    def __init__(self, fam, layout: int = FS_COLBLOCK64, device: str = "cuda:0",
+                 want_row_score: bool = False, want_leaf_idx: bool = False):
+        dev = torch.device(device)
+        self.host = fam
+        self.model = fs_model.from_arrays(fam.model)
+        self.n_rows, self.n_programs, self.k = fam.n_rows, fam.n_programs, fam.k
+        x = torch.from_numpy(np.ascontiguousarray(fam.features)).to(dev)
+        if x.numel() == 0:
+            x = torch.zeros(4, dtype=torch.float32, device=dev)
+        if layout == FS_COLBLOCK64 and fam.n_rows > 0:
+            self.features = fs_pack_colblock64(x, fam.n_rows, fam.model.n_features)
+            torch.cuda.synchronize()
+            del x
+        else:
+            self.features = x
+        self.layout = layout
+        self.prog_off = torch.from_numpy(np.ascontiguousarray(fam.prog_off, dtype=np.int32)).to(dev)
+        self.prog_score = torch.full((max(1, fam.n_programs),), float("nan"), dtype=torch.float32,
+                                     device=dev)
+        self.row_score = (torch.full((max(1, fam.n_rows),), float("nan"), dtype=torch.float32,
+                                     device=dev) if want_row_score else None)
+        self.leaf_idx = (torch.full((max(1, fam.n_rows * fam.model.n_trees),), -1,
+                                    dtype=torch.int16, device=dev) if want_leaf_idx else None)
+        self.topk_idx = torch.full((max(1, fam.k),), -7, dtype=torch.int32, device=dev)
+        self.topk_score = torch.full((max(1, fam.k),), float("nan"), dtype=torch.float32, device=dev)
+
+    def family(self) -> Family:
+        return Family(self.model, self.features, self.layout, self.n_rows, self.prog_off,
+                      self.prog_score, self.row_score, self.leaf_idx)
+
+    def topk_request(self) -> TopkRequest:
+        return TopkRequest(self.prog_score, self.n_programs, self.k, self.topk_idx, self.topk_score)

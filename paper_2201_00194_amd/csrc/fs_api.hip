@@ -1,0 +1,502 @@
+// Host side of the C ABI: argument validation, model packing, descriptor upload, launches.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "fs_internal.h"
+
+namespace fs {
+
+// ---- errors ------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int fail_hip(hipError_t e, const char *what)
+{
+    (void)hipGetLastError();  // clear the sticky launch error, the code is reported here
+    if (e == hipErrorOutOfMemory)
+        return fail(FS_ENOMEM, "%s: %s", what, hipGetErrorString(e));
+    return fail(FS_EDEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+// ---- per-device state: descriptor ring and scratch ---------------------------------------------
+constexpr int kSlots = 8;
+constexpr int kMaxDevices = 16;
+
+struct Slot {
+    void *d_buf = nullptr;
+    void *h_buf = nullptr;  // pinned
+    size_t cap = 0;
+    hipEvent_t done = nullptr;
+    bool used = false;
+};
+
+struct DeviceCtx {
+    Slot slots[kSlots];
+    int next = 0;
+    float *scratch = nullptr;
+    size_t scratch_floats = 0;
+};
+
+static std::mutex g_mu;
+static DeviceCtx g_ctx[kMaxDevices];
+
+static int current_ctx(DeviceCtx **out, int *dev_out = nullptr)
+{
+    int dev = 0;
+    FS_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(FS_EUNSUPPORTED, "device ordinal %d not supported", dev);
+    *out = &g_ctx[dev];
+    if (dev_out)
+        *dev_out = dev;
+    return FS_OK;
+}
+
+// A slot whose previous use has finished, with room for `bytes`.
+static int acquire_slot(DeviceCtx *ctx, size_t bytes, Slot **out)
+{
+    Slot *s = &ctx->slots[ctx->next];
+    ctx->next = (ctx->next + 1) % kSlots;
+    if (!s->done)
+        FS_HIP(hipEventCreateWithFlags(&s->done, hipEventDisableTiming));
+    if (s->used)
+        FS_HIP(hipEventSynchronize(s->done));
+    if (s->cap < bytes) {
+        size_t cap = bytes < 4096 ? 4096 : bytes * 2;
+        if (s->d_buf)
+            FS_HIP(hipFree(s->d_buf));
+        if (s->h_buf)
+            FS_HIP(hipHostFree(s->h_buf));
+        s->d_buf = s->h_buf = nullptr;
+        s->cap = 0;
+        FS_HIP(hipMalloc(&s->d_buf, cap));
+        FS_HIP(hipHostMalloc(&s->h_buf, cap, hipHostMallocDefault));
+        s->cap = cap;
+    }
+    *out = s;
+    return FS_OK;
+}
+
+static int ensure_scratch(DeviceCtx *ctx, size_t floats)
+{
+    if (ctx->scratch_floats >= floats)
+        return FS_OK;
+    // Earlier submissions may still read the old buffer.
+    FS_HIP(hipDeviceSynchronize());
+    if (ctx->scratch)
+        FS_HIP(hipFree(ctx->scratch));
+    ctx->scratch = nullptr;
+    ctx->scratch_floats = 0;
+    size_t want = floats + floats / 4 + 1024;
+    FS_HIP(hipMalloc((void **)&ctx->scratch, want * sizeof(float)));
+    ctx->scratch_floats = want;
+    return FS_OK;
+}
+
+// ---- optional per-kernel timing -------------------------------------------------------------
+struct ProfRecord {
+    hipEvent_t a, b;
+    int kernel_class;
+};
+static std::mutex g_prof_mu;
+static std::vector<ProfRecord> g_prof;
+static size_t g_prof_used = 0;
+static bool g_prof_on = false;
+static bool g_prof_open = false;
+
+void prof_start(int kernel_class, hipStream_t stream)
+{
+    std::lock_guard<std::mutex> lock(g_prof_mu);
+    g_prof_open = false;
+    if (!g_prof_on || g_prof_used >= g_prof.size())
+        return;
+    ProfRecord &r = g_prof[g_prof_used];
+    r.kernel_class = kernel_class;
+    if (hipEventRecord(r.a, stream) == hipSuccess)
+        g_prof_open = true;
+}
+
+void prof_stop(hipStream_t stream)
+{
+    std::lock_guard<std::mutex> lock(g_prof_mu);
+    if (!g_prof_open)
+        return;
+    g_prof_open = false;
+    if (hipEventRecord(g_prof[g_prof_used].b, stream) == hipSuccess)
+        ++g_prof_used;
+}
+
+}  // namespace fs
+
+using namespace fs;
+
+extern "C" int fs_profile_begin(int32_t max_records)
+{
+    std::lock_guard<std::mutex> lock(g_prof_mu);
+    if (max_records < 1 || max_records > (1 << 20))
+        return fail(FS_EINVAL, "fs_profile_begin: max_records %d outside [1, 2^20]", max_records);
+    g_prof_on = false;
+    g_prof_used = 0;
+    while (g_prof.size() < (size_t)max_records) {
+        ProfRecord r;
+        r.kernel_class = 0;
+        FS_HIP(hipEventCreate(&r.a));
+        hipError_t e = hipEventCreate(&r.b);
+        if (e != hipSuccess) {
+            (void)hipEventDestroy(r.a);
+            return fail_hip(e, "hipEventCreate");
+        }
+        try {
+            g_prof.push_back(r);
+        } catch (const std::bad_alloc &) {
+            (void)hipEventDestroy(r.a);
+            (void)hipEventDestroy(r.b);
+            return fail(FS_ENOMEM, "fs_profile_begin: host allocation failed");
+        }
+    }
+    g_prof_on = true;
+    return FS_OK;
+}
+
+extern "C" int fs_profile_end(double *ms_by_kernel, int32_t *launches_by_kernel)
+{
+    std::lock_guard<std::mutex> lock(g_prof_mu);
+    g_prof_on = false;
+    for (int c = 0; c < kKernClasses; ++c) {
+        if (ms_by_kernel) ms_by_kernel[c] = 0.0;
+        if (launches_by_kernel) launches_by_kernel[c] = 0;
+    }
+    for (size_t i = 0; i < g_prof_used; ++i) {
+        FS_HIP(hipEventSynchronize(g_prof[i].b));
+        float ms = 0.f;
+        FS_HIP(hipEventElapsedTime(&ms, g_prof[i].a, g_prof[i].b));
+        const int c = g_prof[i].kernel_class;
+        if (ms_by_kernel) ms_by_kernel[c] += ms;
+        if (launches_by_kernel) launches_by_kernel[c] += 1;
+    }
+    g_prof_used = 0;
+    return FS_OK;
+}
+
+// ---- small entry points ------------------------------------------------------------------------
+extern "C" const char *fs_last_error(void) { return fs::g_err; }
+extern "C" int fs_version(void) { return 100; }
+
+extern "C" int64_t fs_colblock64_floats(int64_t n_rows, int32_t n_features)
+{
+    if (n_rows < 0 || n_features < 0)
+        return 0;
+    return ((n_rows + 63) / 64) * 64 * (int64_t)n_features;
+}
+
+// ---- models ------------------------------------------------------------------------------------
+extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_trees,
+                               const int32_t *tree_off, const int32_t *split_feature,
+                               const float *threshold, const int32_t *left,
+                               const int32_t *right, const float *value, float bias)
+{
+    if (!out)
+        return fail(FS_EINVAL, "fs_model_create: out is NULL");
+    *out = nullptr;
+    if (n_features < 1 || n_features > FS_MAX_FEATURES)
+        return fail(FS_EINVAL, "fs_model_create: n_features %d outside [1, %d]", n_features,
+                    FS_MAX_FEATURES);
+    if (n_trees < 0)
+        return fail(FS_EINVAL, "fs_model_create: n_trees %d is negative", n_trees);
+    if (!tree_off)
+        return fail(FS_EINVAL, "fs_model_create: tree_off is NULL");
+    if (tree_off[0] != 0)
+        return fail(FS_EINVAL, "fs_model_create: tree_off[0] must be 0");
+    for (int t = 0; t < n_trees; ++t) {
+        int64_t sz = (int64_t)tree_off[t + 1] - tree_off[t];
+        if (sz < 1 || sz > FS_MAX_TREE_NODES)
+            return fail(FS_EINVAL, "fs_model_create: tree %d has %lld nodes (allowed 1..%d)", t,
+                        (long long)sz, FS_MAX_TREE_NODES);
+    }
+    const int64_t n_nodes = tree_off[n_trees];
+    if (n_nodes > 0 && (!split_feature || !threshold || !left || !right || !value))
+        return fail(FS_EINVAL, "fs_model_create: a node array is NULL");
+
+    std::vector<GNode> nodes;
+    std::vector<int32_t> depth;
+    try {
+        nodes.resize((size_t)n_nodes);
+        depth.assign((size_t)n_nodes, 0);
+    } catch (const std::bad_alloc &) {
+        return fail(FS_ENOMEM, "fs_model_create: host allocation failed");
+    }
+    int32_t max_depth = 0;
+    for (int t = 0; t < n_trees; ++t) {
+        const int32_t o = tree_off[t];
+        const int32_t sz = tree_off[t + 1] - o;
+        for (int32_t n = 0; n < sz; ++n) {
+            const int32_t g = o + n;
+            GNode nd;
+            if (split_feature[g] < 0) {
+                memcpy(&nd.x, &value[g], 4);
+                nd.y = -1;
+                nd.z = nd.w = g;
+            } else {
+                if (split_feature[g] >= n_features)
+                    return fail(FS_EINVAL, "fs_model_create: tree %d node %d splits on feature %d "
+                                "but the model has %d", t, n, split_feature[g], n_features);
+                if (left[g] <= n || left[g] >= sz || right[g] <= n || right[g] >= sz)
+                    return fail(FS_EINVAL, "fs_model_create: tree %d node %d has child ids "
+                                "(%d, %d); they must lie in (%d, %d)", t, n, left[g], right[g], n, sz);
+                memcpy(&nd.x, &threshold[g], 4);
+                nd.y = split_feature[g];
+                nd.z = o + left[g];
+                nd.w = o + right[g];
+                // children have larger ids, so parents are always finished first
+                const int32_t dl = depth[g] + 1;
+                if (depth[o + left[g]] < dl) depth[o + left[g]] = dl;
+                if (depth[o + right[g]] < dl) depth[o + right[g]] = dl;
+            }
+            if (depth[g] > max_depth)
+                max_depth = depth[g];
+            nodes[(size_t)g] = nd;
+        }
+    }
+
+    fs_model *m = new (std::nothrow) fs_model();
+    if (!m)
+        return fail(FS_ENOMEM, "fs_model_create: host allocation failed");
+    m->n_features = n_features;
+    m->n_trees = n_trees;
+    m->max_depth = max_depth;
+    m->n_nodes = n_nodes;
+    m->bias = bias;
+    m->d_nodes = nullptr;
+    m->d_tree_off = nullptr;
+    hipError_t e = hipGetDevice(&m->device);
+    if (e == hipSuccess)
+        e = hipMalloc((void **)&m->d_tree_off, sizeof(int32_t) * (size_t)(n_trees + 1));
+    if (e == hipSuccess)
+        e = hipMemcpy(m->d_tree_off, tree_off, sizeof(int32_t) * (size_t)(n_trees + 1),
+                      hipMemcpyHostToDevice);
+    if (e == hipSuccess && n_nodes > 0) {
+        e = hipMalloc((void **)&m->d_nodes, sizeof(GNode) * (size_t)n_nodes);
+        if (e == hipSuccess)
+            e = hipMemcpy(m->d_nodes, nodes.data(), sizeof(GNode) * (size_t)n_nodes,
+                          hipMemcpyHostToDevice);
+    }
+    if (e != hipSuccess) {
+        fs_model_destroy(m);
+        return fail_hip(e, "fs_model_create: device upload");
+    }
+    *out = m;
+    return FS_OK;
+}
+
+extern "C" void fs_model_destroy(fs_model *m)
+{
+    if (!m)
+        return;
+    if (m->d_nodes)
+        (void)hipFree(m->d_nodes);
+    if (m->d_tree_off)
+        (void)hipFree(m->d_tree_off);
+    delete m;
+}
+
+// ---- scoring -----------------------------------------------------------------------------------
+extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void *stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    if (n_families < 0)
+        return fail(FS_EINVAL, "fs_score_families: n_families %d is negative", n_families);
+    if (n_families == 0)
+        return FS_OK;
+    if (!fams)
+        return fail(FS_EINVAL, "fs_score_families: fams is NULL");
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx *ctx = nullptr;
+    int dev = 0;
+    int rc = current_ctx(&ctx, &dev);
+    if (rc != FS_OK)
+        return rc;
+
+    size_t scratch_floats = 0;
+    for (int f = 0; f < n_families; ++f) {
+        const fs_family &a = fams[f];
+        if (!a.model)
+            return fail(FS_EINVAL, "fs_score_families: family %d has no model", f);
+        if (a.model->device != dev)
+            return fail(FS_EINVAL, "fs_score_families: family %d: model lives on device %d, "
+                        "current device is %d", f, a.model->device, dev);
+        if (a.n_rows < 0 || a.n_rows >= ((int64_t)1 << 31))
+            return fail(FS_EINVAL, "fs_score_families: family %d: n_rows %lld outside [0, 2^31)", f,
+                        (long long)a.n_rows);
+        if (a.n_programs < 0)
+            return fail(FS_EINVAL, "fs_score_families: family %d: n_programs is negative", f);
+        if (a.layout != FS_ROWMAJOR && a.layout != FS_COLBLOCK64)
+            return fail(FS_EINVAL, "fs_score_families: family %d: unknown layout %d", f, a.layout);
+        if (a.n_rows > 0 && !a.features)
+            return fail(FS_EINVAL, "fs_score_families: family %d: features is NULL", f);
+        if (((uintptr_t)a.features & 15) != 0)
+            return fail(FS_EINVAL, "fs_score_families: family %d: features not 16-byte aligned", f);
+        if (a.n_programs > 0 && !a.prog_off)
+            return fail(FS_EINVAL, "fs_score_families: family %d: prog_off is NULL", f);
+        if (a.n_programs > 0 && !a.prog_score)
+            return fail(FS_EINVAL, "fs_score_families: family %d: prog_score is NULL", f);
+        if (a.n_programs == 0 && a.n_rows != 0)
+            return fail(FS_EINVAL, "fs_score_families: family %d: %lld rows but no programs", f,
+                        (long long)a.n_rows);
+        if (!a.row_score)
+            scratch_floats += (size_t)a.n_rows;
+    }
+    rc = ensure_scratch(ctx, scratch_floats);
+    if (rc != FS_OK)
+        return rc;
+
+    Slot *slot = nullptr;
+    rc = acquire_slot(ctx, sizeof(FamDesc) * (size_t)n_families, &slot);
+    if (rc != FS_OK)
+        return rc;
+    FamDesc *h = (FamDesc *)slot->h_buf;
+    int64_t trav_blocks = 0, seg_blocks = 0;
+    size_t scratch_pos = 0;
+    for (int f = 0; f < n_families; ++f) {
+        const fs_family &a = fams[f];
+        FamDesc d;
+        d.nodes = a.model->d_nodes;
+        d.tree_off = a.model->d_tree_off;
+        d.features = a.features;
+        d.prog_off = a.prog_off;
+        d.prog_score = a.prog_score;
+        if (a.row_score) {
+            d.row_score = a.row_score;
+        } else {
+            d.row_score = ctx->scratch + scratch_pos;
+            scratch_pos += (size_t)a.n_rows;
+        }
+        d.leaf_idx = a.leaf_idx;
+        d.n_trees = a.model->n_trees;
+        d.n_features = a.model->n_features;
+        d.layout = a.layout;
+        d.n_rows = (int32_t)a.n_rows;
+        d.n_programs = a.n_programs;
+        d.bias = a.model->bias;
+        d.trav_block0 = (int32_t)trav_blocks;
+        d.seg_block0 = (int32_t)seg_blocks;
+        trav_blocks += (a.n_rows + kTravRowsPerBlock - 1) / kTravRowsPerBlock;
+        seg_blocks += (a.n_programs + kSegProgsPerBlock - 1) / kSegProgsPerBlock;
+        h[f] = d;
+    }
+    if (trav_blocks >= ((int64_t)1 << 31) || seg_blocks >= ((int64_t)1 << 31))
+        return fail(FS_EUNSUPPORTED, "fs_score_families: too much work for one submission");
+
+    FS_HIP(hipMemcpyAsync(slot->d_buf, slot->h_buf, sizeof(FamDesc) * (size_t)n_families,
+                          hipMemcpyHostToDevice, stream));
+    slot->used = true;
+    const FamDesc *d_desc = (const FamDesc *)slot->d_buf;
+    rc = FS_OK;
+    if (trav_blocks > 0) {
+        prof_start(kKernTraverse, stream);
+        rc = launch_traverse_global(d_desc, n_families, (int)trav_blocks, stream);
+        prof_stop(stream);
+    }
+    if (rc == FS_OK && seg_blocks > 0) {
+        prof_start(kKernSegsum, stream);
+        rc = launch_segsum(d_desc, n_families, (int)seg_blocks, stream);
+        prof_stop(stream);
+    }
+    hipError_t e = hipEventRecord(slot->done, stream);
+    if (rc != FS_OK)
+        return rc;
+    if (e != hipSuccess)
+        return fail_hip(e, "hipEventRecord");
+    return FS_OK;
+}
+
+// ---- top-k -------------------------------------------------------------------------------------
+extern "C" int fs_topk(int32_t n_requests, const fs_topk_req *reqs, void *stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    if (n_requests < 0)
+        return fail(FS_EINVAL, "fs_topk: n_requests %d is negative", n_requests);
+    if (n_requests == 0)
+        return FS_OK;
+    if (!reqs)
+        return fail(FS_EINVAL, "fs_topk: reqs is NULL");
+    int max_k = 0;
+    for (int i = 0; i < n_requests; ++i) {
+        const fs_topk_req &r = reqs[i];
+        if (r.n < 0 || r.k < 0)
+            return fail(FS_EINVAL, "fs_topk: request %d: n=%d k=%d must be non-negative", i, r.n, r.k);
+        if (r.k > FS_MAX_TOPK)
+            return fail(FS_EUNSUPPORTED, "fs_topk: request %d: k=%d exceeds FS_MAX_TOPK=%d", i, r.k,
+                        FS_MAX_TOPK);
+        if (r.n > 0 && !r.score)
+            return fail(FS_EINVAL, "fs_topk: request %d: score is NULL", i);
+        if (r.k > 0 && !r.out_idx)
+            return fail(FS_EINVAL, "fs_topk: request %d: out_idx is NULL", i);
+        if (r.k > max_k)
+            max_k = r.k;
+    }
+    if (max_k == 0)
+        return FS_OK;
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx *ctx = nullptr;
+    int rc = current_ctx(&ctx);
+    if (rc != FS_OK)
+        return rc;
+    Slot *slot = nullptr;
+    rc = acquire_slot(ctx, sizeof(TopkDesc) * (size_t)n_requests, &slot);
+    if (rc != FS_OK)
+        return rc;
+    TopkDesc *h = (TopkDesc *)slot->h_buf;
+    for (int i = 0; i < n_requests; ++i) {
+        h[i].score = reqs[i].score;
+        h[i].out_idx = reqs[i].out_idx;
+        h[i].out_score = reqs[i].out_score;
+        h[i].n = reqs[i].n;
+        h[i].k = reqs[i].k;
+    }
+    FS_HIP(hipMemcpyAsync(slot->d_buf, slot->h_buf, sizeof(TopkDesc) * (size_t)n_requests,
+                          hipMemcpyHostToDevice, stream));
+    slot->used = true;
+    prof_start(kKernTopk, stream);
+    rc = launch_topk((const TopkDesc *)slot->d_buf, n_requests, max_k, stream);
+    prof_stop(stream);
+    hipError_t e = hipEventRecord(slot->done, stream);
+    if (rc != FS_OK)
+        return rc;
+    if (e != hipSuccess)
+        return fail_hip(e, "hipEventRecord");
+    return FS_OK;
+}
+
+// ---- layout helper -----------------------------------------------------------------------------
+extern "C" int fs_pack_colblock64(const float *rowmajor, int64_t n_rows, int32_t n_features,
+                                  float *out, void *stream)
+{
+    if (n_rows < 0 || n_rows >= ((int64_t)1 << 31))
+        return fail(FS_EINVAL, "fs_pack_colblock64: n_rows %lld outside [0, 2^31)", (long long)n_rows);
+    if (n_features < 1 || n_features > FS_MAX_FEATURES)
+        return fail(FS_EINVAL, "fs_pack_colblock64: n_features %d outside [1, %d]", n_features,
+                    FS_MAX_FEATURES);
+    if (n_rows == 0)
+        return FS_OK;
+    if (!rowmajor || !out)
+        return fail(FS_EINVAL, "fs_pack_colblock64: NULL buffer");
+    prof_start(kKernPack, (hipStream_t)stream);
+    int rc = launch_pack_colblock64(rowmajor, n_rows, n_features, out, (hipStream_t)stream);
+    prof_stop((hipStream_t)stream);
+    return rc;
+}

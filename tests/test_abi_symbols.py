@@ -1,0 +1,76 @@
+"""The C-ABI library loads without a GPU and exports every function the header declares."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "familyseer.h")
+LIB = os.path.join(ROOT, "paper_2201_00194_amd", "libfamilyseer.so")
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = re.findall(r"\b(fs_[a-z0-9_]+)\s*\(", src)
+    return sorted(set(names))
+
+
+def test_header_declares_the_named_entry_points():
+    names = declared_functions()
+    for must in ("fs_score_families", "fs_topk", "fs_model_create", "fs_model_destroy",
+                 "fs_pack_colblock64", "fs_last_error", "fs_version"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(LIB):
+        from paper_2201_00194_amd import build
+        build.build()
+    lib = ctypes.CDLL(LIB)
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} declared in familyseer.h but not exported"
+    lib.fs_version.restype = ctypes.c_int
+    assert lib.fs_version() >= 100
+    lib.fs_last_error.restype = ctypes.c_char_p
+    assert lib.fs_last_error() is not None
+
+
+def test_host_side_validation_needs_no_gpu():
+    """Argument errors are found on the host before any device work."""
+    if not os.path.exists(LIB):
+        from paper_2201_00194_amd import build
+        build.build()
+    lib = ctypes.CDLL(LIB)
+    lib.fs_last_error.restype = ctypes.c_char_p
+    lib.fs_colblock64_floats.restype = ctypes.c_int64
+    lib.fs_colblock64_floats.argtypes = [ctypes.c_int64, ctypes.c_int32]
+    assert lib.fs_colblock64_floats(65, 164) == 2 * 64 * 164
+    assert lib.fs_colblock64_floats(0, 164) == 0
+    assert lib.fs_score_families(-1, None, None) == -1
+    assert b"negative" in lib.fs_last_error()
+    assert lib.fs_score_families(0, None, None) == 0
+    assert lib.fs_topk(3, None, None) == -1
+    assert lib.fs_topk(0, None, None) == 0
+    h = ctypes.c_void_p()
+    i32 = ctypes.c_int32
+    off = (i32 * 2)(0, 1)
+    sf = (i32 * 1)(-1)
+    z = (ctypes.c_float * 1)(0.0)
+    ch = (i32 * 1)(-1)
+    lib.fs_model_create.argtypes = [ctypes.POINTER(ctypes.c_void_p), i32, i32] + [ctypes.c_void_p] * 6 + [ctypes.c_float]
+    assert lib.fs_model_create(ctypes.byref(h), 0, 1, off, sf, z, ch, ch, z, 0.0) == -1
+    assert lib.fs_model_create(None, 4, 1, off, sf, z, ch, ch, z, 0.0) == -1
+    bad_off = (i32 * 2)(1, 2)
+    assert lib.fs_model_create(ctypes.byref(h), 4, 1, bad_off, sf, z, ch, ch, z, 0.0) == -1
+    # internal node whose child id does not exceed its own: rejected (would allow cycles)
+    off3 = (i32 * 2)(0, 3)
+    sf3 = (i32 * 3)(0, -1, -1)
+    l3 = (i32 * 3)(0, -1, -1)
+    r3 = (i32 * 3)(2, -1, -1)
+    z3 = (ctypes.c_float * 3)(0.0, 0.0, 0.0)
+    assert lib.fs_model_create(ctypes.byref(h), 4, 1, off3, sf3, z3, l3, r3, z3, 0.0) == -1
+    assert b"child" in lib.fs_last_error()
+    sf3b = (i32 * 3)(9, -1, -1)
+    l3b = (i32 * 3)(1, -1, -1)
+    assert lib.fs_model_create(ctypes.byref(h), 4, 1, off3, sf3b, z3, l3b, r3, z3, 0.0) == -1
+    assert b"feature" in lib.fs_last_error()

@@ -1,0 +1,245 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the C ABI.
+
+Bar: leaf indices and top-k indices bit-exact; fp32 scores within 1e-5 relative /
+1e-6 absolute.  The library reproduces the oracle's order of additions, so scores are in
+fact expected to be bit-identical and the tests also assert that.
+"""
+import numpy as np
+import pytest
+
+from paper_2201_00194_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-5, 1e-6
+
+
+@pytest.fixture(scope="module")
+def api():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2201_00194_amd import api as A
+    return A
+
+
+def run_families(api, fams, layout, want_rows=True, want_leaves=True):
+    import torch
+    devs = [api.DeviceFamily(f, layout=layout, want_row_score=want_rows, want_leaf_idx=want_leaves)
+            for f in fams]
+    api.fs_score_families([d.family() for d in devs])
+    api.fs_topk([d.topk_request() for d in devs])
+    torch.cuda.synchronize()
+    return devs
+
+
+def check_family(oracle, fam, dev, check_leaves=True, check_rows=True):
+    m = fam.model
+    rs = oracle.row_scores(m, fam.features)
+    ps = oracle.program_scores(rs, fam.prog_off)
+    if check_leaves and dev.leaf_idx is not None and fam.n_rows * m.n_trees > 0:
+        li = oracle.leaf_indices(m, fam.features)
+        got = dev.leaf_idx.cpu().numpy().view(np.uint16)[: fam.n_rows * m.n_trees]
+        assert np.array_equal(got.reshape(fam.n_rows, m.n_trees).astype(np.int32), li)
+    if check_rows and dev.row_score is not None and fam.n_rows > 0:
+        got = dev.row_score.cpu().numpy()[: fam.n_rows]
+        np.testing.assert_allclose(got, rs, rtol=RTOL, atol=ATOL)
+        assert np.array_equal(got.view(np.uint32), rs.view(np.uint32))
+    if fam.n_programs > 0:
+        got = dev.prog_score.cpu().numpy()[: fam.n_programs]
+        np.testing.assert_allclose(got, ps, rtol=RTOL, atol=ATOL)
+        assert np.array_equal(got.view(np.uint32), ps.view(np.uint32))
+    if fam.k > 0:
+        idx, val = oracle.topk(ps, fam.k)
+        gi = dev.topk_idx.cpu().numpy()[: fam.k]
+        gv = dev.topk_score.cpu().numpy()[: fam.k]
+        assert np.array_equal(gi, idx)
+        assert np.array_equal(gv.view(np.uint32), val.view(np.uint32))
+        # decoupled check: the oracle's cut applied to the device's own scores
+        if fam.n_programs > 0:
+            own = dev.prog_score.cpu().numpy()[: fam.n_programs]
+            idx2, _ = oracle.topk(own, fam.k)
+            assert np.array_equal(gi, idx2)
+
+
+LAYOUTS = [0, 1]
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_cfg0_full_size(api, oracle, layout):
+    case = W.make_case(0, seed=0)
+    devs = run_families(api, case.families, layout)
+    for f, d in zip(case.families, devs):
+        check_family(oracle, f, d)
+
+
+@pytest.mark.parametrize("cfg,scale,trees", [(1, 0.05, 60), (2, 0.004, 40), (3, 0.02, 50),
+                                              (4, 0.03, 40)])
+def test_scaled_configs_all_outputs(api, oracle, cfg, scale, trees):
+    case = W.make_case(cfg, seed=1, scale=scale, trees=trees)
+    devs = run_families(api, case.families, api.FS_COLBLOCK64)
+    for f, d in zip(case.families, devs):
+        check_family(oracle, f, d)
+
+
+def test_scaled_configs_rowmajor(api, oracle):
+    case = W.make_case(3, seed=2, scale=0.01, trees=30)
+    devs = run_families(api, case.families, api.FS_ROWMAJOR)
+    for f, d in zip(case.families, devs):
+        check_family(oracle, f, d)
+
+
+def test_ragged_tails_and_tiny_shapes(api, oracle):
+    fams = []
+    for i, (P, stm, T, dep, q) in enumerate([(1, (1, 1), 1, 0, 0.0), (3, (1, 1), 2, 1, 0.0),
+                                              (65, (1, 3), 7, 3, 0.3), (130, (0, 5), 9, 5, 0.2),
+                                              (257, (63, 64), 3, 2, 0.0), (64, (1, 1), 33, 4, 0.0),
+                                              (1000, (0, 2), 5, 12, 0.3)]):
+        fams.append(W.make_small_family(seed=100 + i, n_programs=P, stmts=stm, n_trees=T, depth=dep,
+                                        early_leaf_q=q, k=[1, 5, 64, 200, 17, 64, 1000][i],
+                                        bias=[0.0, 0.5, -1.25, 3.0, 0.0, 1e-3, 0.0][i]))
+    for layout in LAYOUTS:
+        devs = run_families(api, fams, layout)
+        for f, d in zip(fams, devs):
+            check_family(oracle, f, d)
+
+
+def test_empty_families_zero_trees_and_k_edges(api, oracle):
+    import torch
+    empty = W.make_small_family(seed=7, n_programs=0, stmts=(1, 1), n_trees=3, depth=2, k=4)
+    assert empty.n_rows == 0 and empty.n_programs == 0
+    no_rows = W.make_small_family(seed=8, n_programs=5, stmts=(0, 0), n_trees=3, depth=2, k=3)
+    assert no_rows.n_rows == 0 and no_rows.n_programs == 5
+    no_trees = W.make_small_family(seed=9, n_programs=20, stmts=(1, 4), n_trees=0, depth=0, k=50,
+                                   bias=0.75)
+    k0 = W.make_small_family(seed=10, n_programs=20, stmts=(2, 2), n_trees=4, depth=3, k=0)
+    fams = [empty, no_rows, no_trees, k0]
+    devs = run_families(api, fams, api.FS_COLBLOCK64)
+    for f, d in zip(fams, devs):
+        check_family(oracle, f, d)
+    # empty family: k entries of (-1, -inf)
+    assert np.array_equal(devs[0].topk_idx.cpu().numpy(), [-1] * 4)
+    assert np.all(np.isneginf(devs[0].topk_score.cpu().numpy()))
+    # programs without rows score +0 and rank by index
+    assert np.array_equal(devs[1].topk_idx.cpu().numpy(), [0, 1, 2])
+    # k = 0 leaves the output buffer untouched
+    assert devs[3].topk_idx.cpu().numpy()[0] == -7
+
+
+def test_special_values_in_features_and_thresholds(api, oracle):
+    fam = W.make_small_family(seed=21, n_programs=300, stmts=(1, 6), n_trees=40, depth=6,
+                              early_leaf_q=0.1, k=32)
+    X = fam.features
+    rng = np.random.default_rng(3)
+    for val in (np.nan, np.inf, -np.inf, -0.0, 1e-42, -1e-42):
+        r = rng.integers(0, X.shape[0], 200)
+        c = rng.integers(0, X.shape[1], 200)
+        X[r, c] = val
+    internal = np.flatnonzero(fam.model.split_feature >= 0)
+    pick = rng.choice(internal, 40, replace=False)
+    fam.model.threshold[pick[:10]] = np.inf
+    fam.model.threshold[pick[10:20]] = -0.0
+    fam.model.threshold[pick[20:30]] = np.nan
+    fam.model.threshold[pick[30:]] = 1e-42
+    for layout in LAYOUTS:
+        devs = run_families(api, [fam], layout)
+        check_family(oracle, fam, devs[0])
+
+
+def test_topk_standalone_ties_signed_zero_nan(api, oracle):
+    import torch
+    rng = np.random.default_rng(5)
+    cases = []
+    s = rng.standard_normal(5000).astype(np.float32)
+    s[rng.integers(0, 5000, 2500)] = s[rng.integers(0, 5000, 2500)]
+    cases.append((s, 100))
+    cases.append((s, 5000))
+    cases.append((s, 6000))
+    cases.append((np.full(3000, 1.5, np.float32), 77))
+    z = np.zeros(2000, np.float32)
+    z[::3] = -0.0
+    z[5::7] = np.nan
+    z[1::11] = -np.inf
+    z[2::13] = np.inf
+    cases.append((z, 1500))
+    cases.append((z, 2000))
+    cases.append((np.array([3.0], np.float32), 1))
+    cases.append((rng.standard_normal(70000).astype(np.float32), 16384))
+    q = (rng.integers(-8, 8, 100000) / 4.0).astype(np.float32)       # few distinct values
+    cases.append((q, 1024))
+    reqs, outs = [], []
+    for sc, k in cases:
+        t = torch.from_numpy(sc).cuda()
+        oi = torch.full((k,), -7, dtype=torch.int32, device="cuda")
+        ov = torch.full((k,), float("nan"), dtype=torch.float32, device="cuda")
+        reqs.append(api.TopkRequest(t, sc.shape[0], k, oi, ov))
+        outs.append((oi, ov))
+    api.fs_topk(reqs)
+    torch.cuda.synchronize()
+    for (sc, k), (oi, ov) in zip(cases, outs):
+        idx, val = oracle.topk(sc, k)
+        assert np.array_equal(oi.cpu().numpy(), idx)
+        assert np.array_equal(ov.cpu().numpy().view(np.uint32), val.view(np.uint32))
+    # out_score may be NULL
+    sc, k = cases[0]
+    oi = torch.full((k,), -7, dtype=torch.int32, device="cuda")
+    api.fs_topk([api.TopkRequest(reqs[0].score, sc.shape[0], k, oi, None)])
+    torch.cuda.synchronize()
+    assert np.array_equal(oi.cpu().numpy(), oracle.topk(sc, k)[0])
+
+
+def test_repeat_calls_are_bit_identical_and_scratch_row_scores_work(api, oracle):
+    import torch
+    case = W.make_case(3, seed=4, scale=0.01, trees=25)
+    devs = [api.DeviceFamily(f, layout=api.FS_COLBLOCK64) for f in case.families]  # no row_score
+    prepared = api.PreparedFamilies([d.family() for d in devs])
+    api.fs_score_families(prepared)
+    torch.cuda.synchronize()
+    first = [d.prog_score.clone() for d in devs]
+    for d in devs:
+        d.prog_score.fill_(float("nan"))
+    api.fs_score_families(prepared)
+    api.fs_topk([d.topk_request() for d in devs])
+    torch.cuda.synchronize()
+    for f, d, a in zip(case.families, devs, first):
+        assert torch.equal(d.prog_score.view(torch.int32), a.view(torch.int32))
+        check_family(oracle, f, d)
+
+
+def test_pack_colblock64_layout(api):
+    import torch
+    for R, D in ((1, 164), (64, 164), (200, 164), (130, 7), (70, 300)):
+        x = torch.arange(R * D, dtype=torch.float32, device="cuda").reshape(R, D)
+        out = api.fs_pack_colblock64(x, R, D)
+        torch.cuda.synchronize()
+        tiles = (R + 63) // 64
+        o = out.cpu().numpy().reshape(tiles, D, 64)
+        xp = np.zeros((tiles * 64, D), np.float32)
+        xp[:R] = x.cpu().numpy()
+        assert np.array_equal(o, xp.reshape(tiles, 64, D).transpose(0, 2, 1))
+
+
+def test_errors_are_reported_not_raised_as_faults(api):
+    import torch
+    fam = W.make_small_family(seed=31, n_programs=10, stmts=(2, 2), n_trees=2, depth=2, k=4)
+    d = api.DeviceFamily(fam)
+    bad = d.family()
+    bad.layout = 9
+    with pytest.raises(api.FsError) as e:
+        api.fs_score_families([bad])
+    assert e.value.code == api.FS_EINVAL and "layout" in str(e.value)
+    bad = d.family()
+    bad.prog_score = None
+    with pytest.raises(api.FsError):
+        api.fs_score_families([bad])
+    bad = d.family()
+    bad.features = None
+    with pytest.raises(api.FsError):
+        api.fs_score_families([bad])
+    with pytest.raises(api.FsError) as e:
+        api.fs_topk([api.TopkRequest(d.prog_score, 10, api.FS_MAX_TOPK + 1, d.topk_idx, None)])
+    assert e.value.code == api.FS_EUNSUPPORTED
+    with pytest.raises(api.FsError):
+        api.fs_topk([api.TopkRequest(d.prog_score, -1, 2, d.topk_idx, None)])
+    # the library still works afterwards
+    api.fs_score_families([d.family()])
+    torch.cuda.synchronize()
