@@ -174,8 +174,11 @@ int64_t fs_colblock64_floats(int64_t n_rows, int32_t n_features);
 /* ---- per-kernel timing (measurement aid) ----------------------------------------------------- */
 
 /* Kernel classes reported by fs_profile_end. */
-enum { FS_KERNEL_TRAVERSE = 0, FS_KERNEL_SEGSUM = 1, FS_KERNEL_TOPK = 2, FS_KERNEL_PACK = 3,
-       FS_KERNEL_CLASSES = 4 };
+enum { FS_KERNEL_TRAVERSE = 0,        /* LDS-staged traversal (the hot kernel)               */
+       FS_KERNEL_SEGSUM = 1, FS_KERNEL_TOPK = 2, FS_KERNEL_PACK = 3,
+       FS_KERNEL_TRAVERSE_GLOBAL = 4, /* traversal from global memory (models/layouts that
+                                         the LDS kernel does not take)                       */
+       FS_KERNEL_CLASSES = 5 };
 
 /*
  * Between fs_profile_begin and fs_profile_end the library brackets every kernel group it

@@ -74,7 +74,7 @@ _lib.fs_profile_begin.restype = ctypes.c_int
 _lib.fs_profile_begin.argtypes = [ctypes.c_int32]
 _lib.fs_profile_end.restype = ctypes.c_int
 _lib.fs_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), _i32p]
-KERNEL_CLASSES = ("traverse", "segsum", "topk", "pack")
+KERNEL_CLASSES = ("traverse", "segsum", "topk", "pack", "traverse_global")
 
 
 def _check(rc: int) -> None:
@@ -229,8 +229,8 @@ def fs_profile_begin(max_records: int) -> None:
 
 def fs_profile_end() -> dict:
     """{kernel class: (total ms, timed launches)}"""
-    ms = (ctypes.c_double * 4)()
-    cnt = (ctypes.c_int32 * 4)()
+    ms = (ctypes.c_double * len(KERNEL_CLASSES))()
+    cnt = (ctypes.c_int32 * len(KERNEL_CLASSES))()
     _check(_lib.fs_profile_end(ms, cnt))
     return {name: (float(ms[i]), int(cnt[i])) for i, name in enumerate(KERNEL_CLASSES)}
 

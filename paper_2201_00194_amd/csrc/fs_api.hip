@@ -202,116 +202,6 @@ extern "C" int64_t fs_colblock64_floats(int64_t n_rows, int32_t n_features)
     return ((n_rows + 63) / 64) * 64 * (int64_t)n_features;
 }
 
-// ---- models ------------------------------------------------------------------------------------
-extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_trees,
-                               const int32_t *tree_off, const int32_t *split_feature,
-                               const float *threshold, const int32_t *left,
-                               const int32_t *right, const float *value, float bias)
-{
-    if (!out)
-        return fail(FS_EINVAL, "fs_model_create: out is NULL");
-    *out = nullptr;
-    if (n_features < 1 || n_features > FS_MAX_FEATURES)
-        return fail(FS_EINVAL, "fs_model_create: n_features %d outside [1, %d]", n_features,
-                    FS_MAX_FEATURES);
-    if (n_trees < 0)
-        return fail(FS_EINVAL, "fs_model_create: n_trees %d is negative", n_trees);
-    if (!tree_off)
-        return fail(FS_EINVAL, "fs_model_create: tree_off is NULL");
-    if (tree_off[0] != 0)
-        return fail(FS_EINVAL, "fs_model_create: tree_off[0] must be 0");
-    for (int t = 0; t < n_trees; ++t) {
-        int64_t sz = (int64_t)tree_off[t + 1] - tree_off[t];
-        if (sz < 1 || sz > FS_MAX_TREE_NODES)
-            return fail(FS_EINVAL, "fs_model_create: tree %d has %lld nodes (allowed 1..%d)", t,
-                        (long long)sz, FS_MAX_TREE_NODES);
-    }
-    const int64_t n_nodes = tree_off[n_trees];
-    if (n_nodes > 0 && (!split_feature || !threshold || !left || !right || !value))
-        return fail(FS_EINVAL, "fs_model_create: a node array is NULL");
-
-    std::vector<GNode> nodes;
-    std::vector<int32_t> depth;
-    try {
-        nodes.resize((size_t)n_nodes);
-        depth.assign((size_t)n_nodes, 0);
-    } catch (const std::bad_alloc &) {
-        return fail(FS_ENOMEM, "fs_model_create: host allocation failed");
-    }
-    int32_t max_depth = 0;
-    for (int t = 0; t < n_trees; ++t) {
-        const int32_t o = tree_off[t];
-        const int32_t sz = tree_off[t + 1] - o;
-        for (int32_t n = 0; n < sz; ++n) {
-            const int32_t g = o + n;
-            GNode nd;
-            if (split_feature[g] < 0) {
-                memcpy(&nd.x, &value[g], 4);
-                nd.y = -1;
-                nd.z = nd.w = g;
-            } else {
-                if (split_feature[g] >= n_features)
-                    return fail(FS_EINVAL, "fs_model_create: tree %d node %d splits on feature %d "
-                                "but the model has %d", t, n, split_feature[g], n_features);
-                if (left[g] <= n || left[g] >= sz || right[g] <= n || right[g] >= sz)
-                    return fail(FS_EINVAL, "fs_model_create: tree %d node %d has child ids "
-                                "(%d, %d); they must lie in (%d, %d)", t, n, left[g], right[g], n, sz);
-                memcpy(&nd.x, &threshold[g], 4);
-                nd.y = split_feature[g];
-                nd.z = o + left[g];
-                nd.w = o + right[g];
-                // children have larger ids, so parents are always finished first
-                const int32_t dl = depth[g] + 1;
-                if (depth[o + left[g]] < dl) depth[o + left[g]] = dl;
-                if (depth[o + right[g]] < dl) depth[o + right[g]] = dl;
-            }
-            if (depth[g] > max_depth)
-                max_depth = depth[g];
-            nodes[(size_t)g] = nd;
-        }
-    }
-
-    fs_model *m = new (std::nothrow) fs_model();
-    if (!m)
-        return fail(FS_ENOMEM, "fs_model_create: host allocation failed");
-    m->n_features = n_features;
-    m->n_trees = n_trees;
-    m->max_depth = max_depth;
-    m->n_nodes = n_nodes;
-    m->bias = bias;
-    m->d_nodes = nullptr;
-    m->d_tree_off = nullptr;
-    hipError_t e = hipGetDevice(&m->device);
-    if (e == hipSuccess)
-        e = hipMalloc((void **)&m->d_tree_off, sizeof(int32_t) * (size_t)(n_trees + 1));
-    if (e == hipSuccess)
-        e = hipMemcpy(m->d_tree_off, tree_off, sizeof(int32_t) * (size_t)(n_trees + 1),
-                      hipMemcpyHostToDevice);
-    if (e == hipSuccess && n_nodes > 0) {
-        e = hipMalloc((void **)&m->d_nodes, sizeof(GNode) * (size_t)n_nodes);
-        if (e == hipSuccess)
-            e = hipMemcpy(m->d_nodes, nodes.data(), sizeof(GNode) * (size_t)n_nodes,
-                          hipMemcpyHostToDevice);
-    }
-    if (e != hipSuccess) {
-        fs_model_destroy(m);
-        return fail_hip(e, "fs_model_create: device upload");
-    }
-    *out = m;
-    return FS_OK;
-}
-
-extern "C" void fs_model_destroy(fs_model *m)
-{
-    if (!m)
-        return;
-    if (m->d_nodes)
-        (void)hipFree(m->d_nodes);
-    if (m->d_tree_off)
-        (void)hipFree(m->d_tree_off);
-    delete m;
-}
-
 // ---- scoring -----------------------------------------------------------------------------------
 extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void *stream_)
 {
@@ -368,7 +258,8 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
     if (rc != FS_OK)
         return rc;
     FamDesc *h = (FamDesc *)slot->h_buf;
-    int64_t trav_blocks = 0, seg_blocks = 0;
+    int64_t trav_blocks = 0, seg_blocks = 0, lds_blocks = 0;
+    bool dump = false;
     size_t scratch_pos = 0;
     for (int f = 0; f < n_families; ++f) {
         const fs_family &a = fams[f];
@@ -393,11 +284,29 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         d.bias = a.model->bias;
         d.trav_block0 = (int32_t)trav_blocks;
         d.seg_block0 = (int32_t)seg_blocks;
+        d.lds_block0 = (int32_t)lds_blocks;
+        d.image = a.model->d_image;
+        d.chunks = a.model->d_chunks;
+        d.slot_ids = a.model->d_slot_ids;
+        d.n_chunks = a.model->n_chunks;
+        d.lds_tile0 = a.model->lds_tile0;
+        d.lds_tiles = a.model->lds_tiles;
+        d.compact = a.model->compact ? 1 : 0;
+        d.pad = 0;
+        // Column-blocked features and a model that fits the LDS format take the LDS kernel;
+        // everything else is walked from global memory.
+        if (a.model->lds_ok && a.layout == FS_COLBLOCK64) {
+            const int64_t tiles = (a.n_rows + 63) / 64;
+            lds_blocks += (tiles + a.model->lds_tiles - 1) / a.model->lds_tiles;
+            if (a.leaf_idx && a.n_rows > 0)
+                dump = true;
+        } else
         trav_blocks += (a.n_rows + kTravRowsPerBlock - 1) / kTravRowsPerBlock;
         seg_blocks += (a.n_programs + kSegProgsPerBlock - 1) / kSegProgsPerBlock;
         h[f] = d;
     }
-    if (trav_blocks >= ((int64_t)1 << 31) || seg_blocks >= ((int64_t)1 << 31))
+    if (trav_blocks >= ((int64_t)1 << 31) || seg_blocks >= ((int64_t)1 << 31) ||
+        lds_blocks >= ((int64_t)1 << 31))
         return fail(FS_EUNSUPPORTED, "fs_score_families: too much work for one submission");
 
     FS_HIP(hipMemcpyAsync(slot->d_buf, slot->h_buf, sizeof(FamDesc) * (size_t)n_families,
@@ -405,8 +314,13 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
     slot->used = true;
     const FamDesc *d_desc = (const FamDesc *)slot->d_buf;
     rc = FS_OK;
-    if (trav_blocks > 0) {
+    if (lds_blocks > 0) {
         prof_start(kKernTraverse, stream);
+        rc = launch_traverse_lds(d_desc, n_families, (int)lds_blocks, dump, stream);
+        prof_stop(stream);
+    }
+    if (rc == FS_OK && trav_blocks > 0) {
+        prof_start(kKernTraverseGlobal, stream);
         rc = launch_traverse_global(d_desc, n_families, (int)trav_blocks, stream);
         prof_stop(stream);
     }

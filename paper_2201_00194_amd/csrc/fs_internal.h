@@ -29,6 +29,40 @@ int fail_hip(hipError_t e, const char *what);
 //   z: global index of the left child    w: of the right child
 typedef int4 GNode;
 
+// ---- LDS-staged model format -------------------------------------------------------------------
+// The ensemble is cut into chunks.  A chunk is a byte image that is copied verbatim to LDS
+// offset 0:
+//     [n_trees x uint32: byte offset of each tree's root] [nodes ...]   (size multiple of 16)
+// A node is 8 bytes {w0, w1}:
+//     internal: w0 = threshold bits, w1 = (feature * 256) << 16 | byte offset of the LEFT child;
+//               the right child sits right after the left one
+//     leaf:     w0 = value bits,     w1 = (n_features * 256) << 16 | (own offset - 8):
+//               it reads the all-NaN column, fails '<' and so steps back onto itself
+// In "compact" chunks (every tree of the model perfect and of one depth >= 1) leaves are 4-byte
+// values only, laid out after the tree's internal nodes; the last split level then steps by 4.
+struct ChunkHdr {
+    uint32_t byte_off;    // into the packed image
+    uint32_t bytes;       // multiple of 16
+    uint32_t n_trees;
+    uint32_t depth;       // split levels to walk (max over the chunk's trees)
+    uint32_t first_tree;  // model-wide index of the chunk's first tree
+    uint32_t slot_off;    // into the id map: entry [slot_off + (lds byte offset >> 2)]
+    uint32_t group;       // trees a wavefront walks at once in this chunk (1..8)
+    uint32_t pad;
+};
+
+// LDS map of the traversal kernel (bytes):
+//   [0, chunk bytes)                       model chunk
+//   [tile0 - n_trees*tiles*256, tile0)     leaf values [tree in chunk][tile][lane] (fp32)
+//   [tile0, 160 KB)                        `tiles` feature tiles of (n_features+1)*256 bytes,
+//                                          tile0 = 160 KB - tiles * tile bytes
+constexpr int kLdsBytes = 160 * 1024;
+constexpr int kLdsWaves = 12;           // wavefronts per workgroup
+constexpr int kLdsMaxTiles = 3;         // 64-row tiles per workgroup (1, 2 or 3)
+constexpr int kMaxChunkBytes = 65536 - 16;
+constexpr int kMaxChunkTrees = 96;
+constexpr int kPrefetchRegs = 6;        // 16-byte registers per thread for the next chunk
+
 }  // namespace fs
 
 // The opaque model: host copy of what validation needs plus device arrays.
@@ -41,6 +75,16 @@ struct fs_model {
     int device;
     fs::GNode *d_nodes;    // [n_nodes]
     int32_t *d_tree_off;   // [n_trees + 1]
+    // LDS-staged format (absent if the model does not fit it)
+    bool lds_ok;
+    bool compact;          // perfect trees of one depth, 4-byte leaves
+    int32_t lds_tiles;     // 64-row tiles per workgroup chosen for this model
+    int32_t lds_tile0;     // LDS byte offset of the first feature tile
+    int32_t n_chunks;
+    uint8_t *d_image;      // all chunk images back to back
+    fs::ChunkHdr *d_chunks;
+    uint16_t *d_slot_ids;  // caller's local node id per 4-byte slot (leaves only meaningful)
+    size_t image_bytes;
 };
 
 namespace fs {
@@ -60,8 +104,18 @@ struct FamDesc {
     int32_t n_rows;
     int32_t n_programs;
     float bias;
-    int32_t trav_block0;   // first block of the traversal grid that belongs to this family
+    int32_t trav_block0;   // first block of the global-memory traversal grid of this family
     int32_t seg_block0;    // first block of the segmented-sum grid
+    // LDS-staged traversal
+    const uint8_t *image;
+    const ChunkHdr *chunks;
+    const uint16_t *slot_ids;
+    int32_t n_chunks;
+    int32_t lds_tile0;
+    int32_t lds_tiles;
+    int32_t compact;
+    int32_t lds_block0;    // first block of the LDS traversal grid of this family
+    int32_t pad;
 };
 
 struct TopkDesc {
@@ -75,13 +129,16 @@ struct TopkDesc {
 // ---- launchers (each returns FS_OK or records an error) ---------------------------------------
 int launch_traverse_global(const FamDesc *d_desc, int n_families, int total_blocks,
                            hipStream_t stream);
+int launch_traverse_lds(const FamDesc *d_desc, int n_families, int total_blocks, bool dump,
+                        hipStream_t stream);
 int launch_segsum(const FamDesc *d_desc, int n_families, int total_blocks, hipStream_t stream);
 int launch_topk(const TopkDesc *d_desc, int n_requests, int max_k, hipStream_t stream);
 int launch_pack_colblock64(const float *in, int64_t n_rows, int32_t n_features, float *out,
                            hipStream_t stream);
 
 // ---- optional per-kernel timing (fs_profile_begin / fs_profile_end) ----------------------------
-enum KernelClass { kKernTraverse = 0, kKernSegsum = 1, kKernTopk = 2, kKernPack = 3, kKernClasses = 4 };
+enum KernelClass { kKernTraverse = 0, kKernSegsum = 1, kKernTopk = 2, kKernPack = 3,
+                   kKernTraverseGlobal = 4, kKernClasses = 5 };
 // Records an event pair around the launches made between prof_start and prof_stop when
 // profiling is on; no-ops otherwise.  Both run under the API mutex.
 void prof_start(int kernel_class, hipStream_t stream);

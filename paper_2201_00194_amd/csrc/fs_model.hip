@@ -1,0 +1,375 @@
+// fs_model_create / fs_model_destroy: validation of the caller's ensemble and packing into
+// the two device formats (flat global-memory nodes; LDS-staged chunk images).
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "fs_internal.h"
+
+using namespace fs;
+
+namespace {
+
+struct PackedTree {
+    std::vector<uint32_t> words;     // tree image; child offsets relative to the tree start
+    std::vector<uint16_t> slot_ids;  // caller's local id per 4-byte slot
+    std::vector<uint32_t> fix;       // word indices whose low 16 bits need + tree base
+    int depth = 0;
+};
+
+// Breadth-first relabelling that puts the two children of a node next to each other.
+// Returns false if the node graph is not a tree (a shared child), or if compact is asked for
+// and the tree is not perfect of `depth`.
+bool pack_tree(const int32_t *sf, const float *thr, const int32_t *left, const int32_t *right,
+               const float *val, int32_t sz, int n_features, bool compact, int depth,
+               PackedTree *out)
+{
+    std::vector<int32_t> order;
+    std::vector<int32_t> level;
+    order.push_back(0);
+    level.push_back(0);
+    int max_level = 0;
+    for (size_t i = 0; i < order.size(); ++i) {
+        const int32_t n = order[i];
+        if (sf[n] >= 0) {
+            order.push_back(left[n]);
+            level.push_back(level[i] + 1);
+            order.push_back(right[n]);
+            level.push_back(level[i] + 1);
+            if (level[i] + 1 > max_level)
+                max_level = level[i] + 1;
+            if (order.size() > (size_t)sz)
+                return false;   // some node has two parents: not a tree, would unfold without bound
+        }
+    }
+    out->depth = max_level;
+    const size_t n = order.size();
+    // position of the first child of order[i] in `order`: children are appended in visit order
+    std::vector<uint32_t> first_child(n, 0);
+    {
+        uint32_t next = 1;
+        for (size_t i = 0; i < n; ++i)
+            if (sf[order[i]] >= 0) {
+                first_child[i] = next;
+                next += 2;
+            }
+    }
+    const uint32_t nan_col = (uint32_t)n_features * 256u;
+    if (!compact) {
+        out->words.assign(2 * n, 0);
+        out->slot_ids.assign(2 * n, 0);
+        for (size_t i = 0; i < n; ++i) {
+            const int32_t o = order[i];
+            uint32_t w0, w1;
+            if (sf[o] >= 0) {
+                memcpy(&w0, &thr[o], 4);
+                w1 = (((uint32_t)sf[o] * 256u) << 16) | (8u * first_child[i]);
+            } else {
+                memcpy(&w0, &val[o], 4);
+                // own offset - 8; the tree base is at least 8, so this never underflows
+                w1 = (nan_col << 16) | ((8u * (uint32_t)i - 8u) & 0xFFFFu);
+            }
+            out->words[2 * i] = w0;
+            out->words[2 * i + 1] = w1;
+            out->fix.push_back((uint32_t)(2 * i + 1));
+            out->slot_ids[2 * i] = (uint16_t)o;
+            out->slot_ids[2 * i + 1] = (uint16_t)o;
+        }
+        return true;
+    }
+    // compact: internal nodes first (8 bytes), then leaves (4 bytes), both in visit order
+    const size_t n_int = ((size_t)1 << depth) - 1, n_leaf = (size_t)1 << depth;
+    if (n != n_int + n_leaf)
+        return false;
+    for (size_t i = 0; i < n; ++i)
+        if ((sf[order[i]] >= 0) != (i < n_int) || level[i] != (i < n_int ? level[i] : depth))
+            return false;
+    out->words.assign(2 * n_int + n_leaf, 0);
+    out->slot_ids.assign(2 * n_int + n_leaf, 0);
+    for (size_t i = 0; i < n_int; ++i) {
+        const int32_t o = order[i];
+        uint32_t w0;
+        memcpy(&w0, &thr[o], 4);
+        const uint32_t c = first_child[i];
+        const uint32_t child_off = (c < n_int) ? 8u * c : (uint32_t)(8u * n_int + 4u * (c - n_int));
+        out->words[2 * i] = w0;
+        out->words[2 * i + 1] = (((uint32_t)sf[o] * 256u) << 16) | child_off;
+        out->fix.push_back((uint32_t)(2 * i + 1));
+        out->slot_ids[2 * i] = out->slot_ids[2 * i + 1] = (uint16_t)o;
+    }
+    for (size_t j = 0; j < n_leaf; ++j) {
+        const int32_t o = order[n_int + j];
+        memcpy(&out->words[2 * n_int + j], &val[o], 4);
+        out->slot_ids[2 * n_int + j] = (uint16_t)o;
+    }
+    return true;
+}
+
+// Depth of every leaf equal to `*depth` (set from the first leaf) and the tree perfect?
+bool tree_is_perfect(const int32_t *sf, const int32_t *left, const int32_t *right, int32_t sz,
+                     int *depth)
+{
+    std::vector<int32_t> lev((size_t)sz, -1);
+    lev[0] = 0;
+    int64_t reach = 0;
+    int d = -1;
+    for (int32_t n = 0; n < sz; ++n) {       // children have larger ids: one forward pass
+        if (lev[n] < 0)
+            continue;
+        ++reach;
+        if (sf[n] >= 0) {
+            if (lev[left[n]] >= 0 || lev[right[n]] >= 0 || left[n] == right[n])
+                return false;                // shared child: not a tree
+            lev[left[n]] = lev[right[n]] = lev[n] + 1;
+        } else {
+            if (d < 0)
+                d = lev[n];
+            else if (d != lev[n])
+                return false;
+        }
+    }
+    if (d < 1 || d > 14 || reach != ((int64_t)2 << d) - 1)
+        return false;
+    if (*depth < 0)
+        *depth = d;
+    return *depth == d;
+}
+
+void free_device(fs_model *m)
+{
+    if (m->d_nodes) (void)hipFree(m->d_nodes);
+    if (m->d_tree_off) (void)hipFree(m->d_tree_off);
+    if (m->d_image) (void)hipFree(m->d_image);
+    if (m->d_chunks) (void)hipFree(m->d_chunks);
+    if (m->d_slot_ids) (void)hipFree(m->d_slot_ids);
+}
+
+template <typename T>
+hipError_t upload(T **dst, const std::vector<T> &src)
+{
+    *dst = nullptr;
+    if (src.empty())
+        return hipSuccess;
+    hipError_t e = hipMalloc((void **)dst, src.size() * sizeof(T));
+    if (e != hipSuccess)
+        return e;
+    return hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice);
+}
+
+}  // namespace
+
+extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_trees,
+                               const int32_t *tree_off, const int32_t *split_feature,
+                               const float *threshold, const int32_t *left,
+                               const int32_t *right, const float *value, float bias)
+{
+    if (!out)
+        return fail(FS_EINVAL, "fs_model_create: out is NULL");
+    *out = nullptr;
+    if (n_features < 1 || n_features > FS_MAX_FEATURES)
+        return fail(FS_EINVAL, "fs_model_create: n_features %d outside [1, %d]", n_features,
+                    FS_MAX_FEATURES);
+    if (n_trees < 0)
+        return fail(FS_EINVAL, "fs_model_create: n_trees %d is negative", n_trees);
+    if (!tree_off)
+        return fail(FS_EINVAL, "fs_model_create: tree_off is NULL");
+    if (tree_off[0] != 0)
+        return fail(FS_EINVAL, "fs_model_create: tree_off[0] must be 0");
+    for (int t = 0; t < n_trees; ++t) {
+        int64_t sz = (int64_t)tree_off[t + 1] - tree_off[t];
+        if (sz < 1 || sz > FS_MAX_TREE_NODES)
+            return fail(FS_EINVAL, "fs_model_create: tree %d has %lld nodes (allowed 1..%d)", t,
+                        (long long)sz, FS_MAX_TREE_NODES);
+    }
+    const int64_t n_nodes = tree_off[n_trees];
+    if (n_nodes > 0 && (!split_feature || !threshold || !left || !right || !value))
+        return fail(FS_EINVAL, "fs_model_create: a node array is NULL");
+
+    try {
+        // ---- validation + flat format ----
+        std::vector<GNode> nodes((size_t)n_nodes);
+        std::vector<int32_t> depth((size_t)n_nodes, 0);
+        int32_t max_depth = 0;
+        for (int t = 0; t < n_trees; ++t) {
+            const int32_t o = tree_off[t];
+            const int32_t sz = tree_off[t + 1] - o;
+            for (int32_t n = 0; n < sz; ++n) {
+                const int32_t g = o + n;
+                GNode nd;
+                if (split_feature[g] < 0) {
+                    memcpy(&nd.x, &value[g], 4);
+                    nd.y = -1;
+                    nd.z = nd.w = g;
+                } else {
+                    if (split_feature[g] >= n_features)
+                        return fail(FS_EINVAL, "fs_model_create: tree %d node %d splits on feature "
+                                    "%d but the model has %d", t, n, split_feature[g], n_features);
+                    if (left[g] <= n || left[g] >= sz || right[g] <= n || right[g] >= sz)
+                        return fail(FS_EINVAL, "fs_model_create: tree %d node %d has child ids "
+                                    "(%d, %d); they must lie in (%d, %d)", t, n, left[g], right[g],
+                                    n, sz);
+                    memcpy(&nd.x, &threshold[g], 4);
+                    nd.y = split_feature[g];
+                    nd.z = o + left[g];
+                    nd.w = o + right[g];
+                    const int32_t dl = depth[g] + 1;   // parents come before their children
+                    if (depth[o + left[g]] < dl) depth[o + left[g]] = dl;
+                    if (depth[o + right[g]] < dl) depth[o + right[g]] = dl;
+                }
+                if (depth[g] > max_depth)
+                    max_depth = depth[g];
+                nodes[(size_t)g] = nd;
+            }
+        }
+
+        fs_model *m = new (std::nothrow) fs_model();
+        if (!m)
+            return fail(FS_ENOMEM, "fs_model_create: host allocation failed");
+        memset(m, 0, sizeof(*m));
+        m->n_features = n_features;
+        m->n_trees = n_trees;
+        m->max_depth = max_depth;
+        m->n_nodes = n_nodes;
+        m->bias = bias;
+
+        // ---- LDS-staged format ----
+        std::vector<uint8_t> image;
+        std::vector<ChunkHdr> chunks;
+        std::vector<uint16_t> slot_ids;
+        const int tile_bytes = (n_features + 1) * 256;
+        if (n_trees > 0 && n_features <= 255) {
+            int common_depth = -1;
+            bool compact = true;
+            for (int t = 0; t < n_trees && compact; ++t) {
+                const int32_t o = tree_off[t];
+                compact = tree_is_perfect(split_feature + o, left + o, right + o,
+                                          tree_off[t + 1] - o, &common_depth);
+            }
+            std::vector<PackedTree> trees((size_t)n_trees);
+            size_t max_tree = 0, sum_tree = 0;
+            bool all_trees = true;
+            for (int t = 0; t < n_trees && all_trees; ++t) {
+                const int32_t o = tree_off[t];
+                all_trees = pack_tree(split_feature + o, threshold + o, left + o, right + o,
+                                      value + o, tree_off[t + 1] - o, n_features, compact,
+                                      common_depth, &trees[(size_t)t]);
+                const size_t b = trees[(size_t)t].words.size() * 4;
+                max_tree = b > max_tree ? b : max_tree;
+                sum_tree += b;
+            }
+            const size_t avg_tree = sum_tree / (size_t)n_trees;
+            // Pick the number of row tiles per workgroup.  More tiles mean fewer passes of the
+            // model through LDS, but less room for trees; what hides LDS latency is the number
+            // of independent walks in flight, tiles x trees resident, so that comes first.
+            int best_t = 0, best_score = -1;
+            size_t best_avail = 0;
+            for (int nt = all_trees ? kLdsMaxTiles : 0; nt >= 1; --nt) {
+                const long avail = (long)kLdsBytes - (long)nt * tile_bytes - 64;
+                const size_t per_tree_val = (size_t)nt * 256;
+                if (avail < (long)(max_tree + 16 + per_tree_val))
+                    continue;
+                size_t by_chunk = ((size_t)kMaxChunkBytes - 16) / (avg_tree + 4);
+                size_t by_avail = ((size_t)avail - 16) / (avg_tree + 4 + per_tree_val);
+                size_t per = by_chunk < by_avail ? by_chunk : by_avail;
+                if (per < 1) per = 1;
+                if (per > (size_t)kMaxChunkTrees) per = kMaxChunkTrees;
+                int score = nt * (int)per;
+                if (score > 24) score = 24;
+                if (score > best_score) {
+                    best_score = score;
+                    best_t = nt;
+                    best_avail = (size_t)avail;
+                }
+            }
+            if (best_t > 0) {
+                const size_t per_tree_val = (size_t)best_t * 256;
+                const int slots = kLdsWaves / best_t;
+                m->lds_ok = true;
+                m->compact = compact;
+                m->lds_tiles = best_t;
+                int t = 0;
+                while (t < n_trees) {
+                    // how many trees fit: chunk image (table included) + their value rows
+                    int cnt = 0;
+                    size_t body = 0;
+                    while (t + cnt < n_trees && cnt < kMaxChunkTrees) {
+                        const size_t b = trees[(size_t)(t + cnt)].words.size() * 4;
+                        const size_t table = ((size_t)(cnt + 1) * 4 + 7) & ~(size_t)7;
+                        const size_t img = (table + body + b + 15) & ~(size_t)15;
+                        if (img > (size_t)kMaxChunkBytes ||
+                            img + (size_t)(cnt + 1) * per_tree_val > best_avail)
+                            break;
+                        body += b;
+                        ++cnt;
+                    }
+                    // cnt >= 1 by the choice of best_t
+                    const size_t table = ((size_t)cnt * 4 + 7) & ~(size_t)7;
+                    const size_t bytes = (table + body + 15) & ~(size_t)15;
+                    ChunkHdr h;
+                    memset(&h, 0, sizeof(h));
+                    h.byte_off = (uint32_t)image.size();
+                    h.bytes = (uint32_t)bytes;
+                    h.n_trees = (uint32_t)cnt;
+                    h.first_tree = (uint32_t)t;
+                    h.slot_off = (uint32_t)slot_ids.size();
+                    // trees per walk: spread the chunk's trees evenly over the wavefronts that
+                    // share a tile, at most 8 at a time
+                    const int rounds = (cnt + 8 * slots - 1) / (8 * slots);
+                    h.group = (uint32_t)((cnt + slots * rounds - 1) / (slots * rounds));
+                    image.resize(image.size() + bytes, 0);
+                    slot_ids.resize(slot_ids.size() + bytes / 4, 0);
+                    uint8_t *img = image.data() + h.byte_off;
+                    uint16_t *ids = slot_ids.data() + h.slot_off;
+                    size_t pos = table;
+                    uint32_t dmax = 0;
+                    for (int j = 0; j < cnt; ++j) {
+                        PackedTree &pt = trees[(size_t)(t + j)];
+                        const uint32_t base = (uint32_t)pos;
+                        memcpy(img + 4 * j, &base, 4);
+                        for (uint32_t wi : pt.fix) {
+                            const uint32_t w = pt.words[wi];
+                            pt.words[wi] = (w & 0xFFFF0000u) | (((w & 0xFFFFu) + base) & 0xFFFFu);
+                        }
+                        memcpy(img + pos, pt.words.data(), pt.words.size() * 4);
+                        memcpy(ids + pos / 4, pt.slot_ids.data(), pt.slot_ids.size() * 2);
+                        pos += pt.words.size() * 4;
+                        if ((uint32_t)pt.depth > dmax) dmax = (uint32_t)pt.depth;
+                    }
+                    h.depth = dmax;
+                    chunks.push_back(h);
+                    t += cnt;
+                }
+                m->n_chunks = (int32_t)chunks.size();
+                m->image_bytes = image.size();
+                m->lds_tile0 = kLdsBytes - best_t * tile_bytes;
+            }
+        }
+
+        hipError_t e = hipGetDevice(&m->device);
+        if (e == hipSuccess) {
+            std::vector<int32_t> toff(tree_off, tree_off + n_trees + 1);
+            e = upload(&m->d_tree_off, toff);
+        }
+        if (e == hipSuccess) e = upload(&m->d_nodes, nodes);
+        if (e == hipSuccess) e = upload(&m->d_image, image);
+        if (e == hipSuccess) e = upload(&m->d_chunks, chunks);
+        if (e == hipSuccess) e = upload(&m->d_slot_ids, slot_ids);
+        if (e != hipSuccess) {
+            free_device(m);
+            delete m;
+            return fail_hip(e, "fs_model_create: device upload");
+        }
+        *out = m;
+        return FS_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(FS_ENOMEM, "fs_model_create: host allocation failed");
+    }
+}
+
+extern "C" void fs_model_destroy(fs_model *m)
+{
+    if (!m)
+        return;
+    free_device(m);
+    delete m;
+}

@@ -1,0 +1,289 @@
+// LDS-staged traversal: the hot kernel of fs_score_families.
+//
+// The family's model estimates every candidate (Section 4.2 of the paper); here that is,
+// per statement row, a walk through every tree and a sum of the reached leaves in tree
+// order.
+//
+// A workgroup of 12 wavefronts holds up to three 64-row feature tiles in LDS in the
+// column-blocked layout they have in HBM: row l of a tile is lane l, and column j sits at
+// j*256 + l*4, so a gather of 64 different features by 64 lanes touches 64 different
+// words in 64 different banks (no conflict whatever the features are).  The model streams
+// through LDS in chunks.  The wavefronts that share a tile split the chunk's trees among
+// themselves and every lane walks several trees at once; that keeps 24 or more independent
+// walks in flight per compute unit, which is what hides the LDS latency.  Each walk ends
+// by parking its leaf value in LDS; one wavefront per tile then adds the chunk's values to
+// the row's running sum in tree order, so the row score has the bits of a plain
+// sequential fp32 sum.  The next chunk is fetched into registers while the current one is
+// being walked.
+//
+// LDS map:  [0, chunk bytes)                    current model chunk (node offsets are
+//                                               absolute LDS addresses)
+//           [tile0 - trees*tiles*256, tile0)    leaf values [tree][tile][lane]
+//           [tile0 + t*tile, ... + tile)        tile t, tile = (F+1)*256 B; column F is all
+//                                               NaN: a leaf "splits" on it, fails '<' and
+//                                               stays where it is
+#include "fs_internal.h"
+
+namespace fs {
+
+extern __shared__ __attribute__((aligned(16))) unsigned char fs_lds[];   // sized at launch
+
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// LDS accesses by absolute byte address (the dynamic LDS block starts at address 0: the
+// kernel has no static LDS).
+#if defined(__HIP_DEVICE_COMPILE__)
+#define FS_LDS_PTR(T, a) ((__attribute__((address_space(3))) T *)(uint32_t)(a))
+#else
+#define FS_LDS_PTR(T, a) ((T *)(uintptr_t)(a))   // host pass only parses the kernels
+#endif
+__device__ __forceinline__ u32x2 lds_u2(uint32_t a) { return *FS_LDS_PTR(const u32x2, a); }
+__device__ __forceinline__ float lds_f(uint32_t a) { return *FS_LDS_PTR(const float, a); }
+__device__ __forceinline__ uint32_t lds_u(uint32_t a) { return *FS_LDS_PTR(const uint32_t, a); }
+__device__ __forceinline__ void lds_store_u4(uint32_t a, u32x4 v) { *FS_LDS_PTR(u32x4, a) = v; }
+__device__ __forceinline__ void lds_store_f(uint32_t a, float v) { *FS_LDS_PTR(float, a) = v; }
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Walk K trees of the current chunk for this lane's row.  root[k] are LDS byte offsets; on
+// return a[k] is the LDS offset of the leaf reached and v[k] its value.
+// COMPACT: perfect trees with 4-byte leaves, so the last split level steps by 4.
+template <int K, bool COMPACT>
+__device__ __forceinline__ void walk_group(const uint32_t (&root)[K], int depth,
+                                           uint32_t lane_base, uint32_t (&a)[K], float (&v)[K])
+{
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+        a[k] = root[k];
+    const int full_levels = COMPACT ? depth - 1 : depth;
+    for (int l = 0; l < full_levels; ++l) {
+        u32x2 nd[K];
+        float x[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            nd[k] = lds_u2(a[k]);
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            x[k] = lds_f((nd[k].y >> 16) + lane_base);
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            a[k] = (nd[k].y & 0xFFFFu) + ((x[k] < __uint_as_float(nd[k].x)) ? 0u : 8u);
+    }
+    if (COMPACT) {
+        u32x2 nd[K];
+        float x[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            nd[k] = lds_u2(a[k]);
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            x[k] = lds_f((nd[k].y >> 16) + lane_base);
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            a[k] = (nd[k].y & 0xFFFFu) + ((x[k] < __uint_as_float(nd[k].x)) ? 0u : 4u);
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+        v[k] = lds_f(a[k]);
+}
+
+// Trees [g, g+K) of the chunk: walk, park the leaf values, optionally report the leaf ids.
+template <int K, bool COMPACT, bool DUMP>
+__device__ __forceinline__ void walk_k(int g, int depth, uint32_t lane_base, uint32_t val_addr,
+                                       uint32_t val_stride, const uint16_t *slot_ids,
+                                       uint16_t *leaf_out)
+{
+    uint32_t root[K], a[K];
+    float v[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+        root[k] = lds_u(4u * (uint32_t)(g + k));        // same address in every lane: broadcast
+    walk_group<K, COMPACT>(root, depth, lane_base, a, v);
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+        lds_store_f(val_addr + (uint32_t)(g + k) * val_stride, v[k]);
+    if (DUMP) {
+        if (leaf_out) {
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+                leaf_out[g + k] = slot_ids[a[k] >> 2];
+        }
+    }
+}
+
+template <bool COMPACT, bool DUMP>
+__device__ __forceinline__ void walk_n(int count, int g, int depth, uint32_t lane_base,
+                                       uint32_t val_addr, uint32_t val_stride,
+                                       const uint16_t *slot_ids, uint16_t *leaf_out)
+{
+    switch (count) {
+    case 8: walk_k<8, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 7: walk_k<7, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 6: walk_k<6, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 5: walk_k<5, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 4: walk_k<4, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 3: walk_k<3, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 2: walk_k<2, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 1: walk_k<1, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    default: break;
+    }
+}
+
+constexpr int kLdsThreads = 64 * kLdsWaves;
+
+template <bool DUMP>
+__global__ void __launch_bounds__(kLdsThreads)
+traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families)
+{
+    int lo = 0, hi = n_families - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (descs[mid].lds_block0 <= (int)blockIdx.x)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    const FamDesc &d = descs[lo];
+    const int tid = threadIdx.x;
+    const int wave = uniform(tid >> 6), lane = tid & 63;
+    const int T = d.lds_tiles;                  // tiles per workgroup
+    const int S = kLdsWaves / T;                // wavefronts sharing a tile
+    const int my_tile = wave % T, my_slot = wave / T;
+    const int n_tiles = (d.n_rows + 63) >> 6;
+    const int tile_first = (blockIdx.x - d.lds_block0) * T;
+    const int tiles_here = min(T, n_tiles - tile_first);
+    const bool active = my_tile < tiles_here;
+    const int F = d.n_features;
+    const uint32_t tile_bytes = (uint32_t)(F + 1) * 256u;
+    const uint32_t tile0 = (uint32_t)d.lds_tile0;
+    const uint32_t lane_base = tile0 + (uint32_t)my_tile * tile_bytes + 4u * (uint32_t)lane;
+
+    // ---- feature tiles: consecutive tiles are one contiguous run in HBM ----
+    {
+        const u32x4 *src = (const u32x4 *)(d.features + (int64_t)tile_first * F * 64);
+        const int per_tile = F * 16;                       // 16-byte pieces per tile
+        const int n16 = tiles_here * per_tile;
+        for (int i = tid; i < n16; i += kLdsThreads) {
+            const int t = i / per_tile, j = i - t * per_tile;
+            lds_store_u4(tile0 + (uint32_t)t * tile_bytes + 16u * (uint32_t)j, src[i]);
+        }
+        if (tid < 64 * tiles_here)
+            lds_store_f(tile0 + (uint32_t)(tid >> 6) * tile_bytes + (uint32_t)F * 256u +
+                            4u * (uint32_t)(tid & 63), __builtin_nanf(""));
+    }
+
+    const int r = (tile_first + my_tile) * 64 + lane;
+    float acc = d.bias;
+    uint16_t *leaf_row = nullptr;
+    if (DUMP) {
+        if (active && d.leaf_idx && r < d.n_rows)
+            leaf_row = d.leaf_idx + (int64_t)r * d.n_trees;
+    }
+    const bool compact = d.compact != 0;
+    const int n_chunks = d.n_chunks;
+    const uint32_t val_stride = (uint32_t)T * 256u;        // bytes between trees' value rows
+
+    // ---- first chunk ----
+    u32x4 pf[kPrefetchRegs];
+    ChunkHdr h = d.chunks[0];
+    {
+        const u32x4 *src = (const u32x4 *)(d.image + h.byte_off);
+        const int n16 = (int)(h.bytes >> 4);
+#pragma unroll
+        for (int j = 0; j < kPrefetchRegs; ++j) {
+            const int i = tid + j * kLdsThreads;
+            if (i < n16)
+                pf[j] = src[i];
+        }
+#pragma unroll
+        for (int j = 0; j < kPrefetchRegs; ++j) {
+            const int i = tid + j * kLdsThreads;
+            if (i < n16)
+                lds_store_u4(16u * (uint32_t)i, pf[j]);
+        }
+    }
+    __syncthreads();
+
+    for (int c = 0; c < n_chunks; ++c) {
+        ChunkHdr hn = h;
+        int n16_next = 0;
+        if (c + 1 < n_chunks) {                            // next chunk: global -> registers
+            hn = d.chunks[c + 1];
+            const u32x4 *src = (const u32x4 *)(d.image + hn.byte_off);
+            n16_next = (int)(hn.bytes >> 4);
+#pragma unroll
+            for (int j = 0; j < kPrefetchRegs; ++j) {
+                const int i = tid + j * kLdsThreads;
+                if (i < n16_next)
+                    pf[j] = src[i];
+            }
+        }
+        const int n = uniform((int)h.n_trees);
+        const int depth = uniform((int)h.depth);
+        const int group = uniform((int)h.group);
+        const uint32_t val0 = tile0 - (uint32_t)n * val_stride;   // packing keeps it above the image
+        if (active) {
+            const uint32_t val_addr = val0 + (uint32_t)my_tile * 256u + 4u * (uint32_t)lane;
+            const uint16_t *ids = d.slot_ids + h.slot_off;
+            uint16_t *leaf_out = leaf_row ? leaf_row + h.first_tree : nullptr;
+            for (int g = my_slot * group; g < n; g += S * group) {
+                const int count = min(group, n - g);
+                if (compact)
+                    walk_n<true, DUMP>(count, g, depth, lane_base, val_addr, val_stride, ids, leaf_out);
+                else
+                    walk_n<false, DUMP>(count, g, depth, lane_base, val_addr, val_stride, ids, leaf_out);
+            }
+        }
+        __syncthreads();       // every walk of this chunk is done and its values are parked
+        if (active && my_slot == 0) {
+            uint32_t va = val0 + (uint32_t)my_tile * 256u + 4u * (uint32_t)lane;
+            for (int t = 0; t < n; ++t) {
+                acc = acc + lds_f(va);
+                va += val_stride;
+            }
+        }
+        if (c + 1 < n_chunks) {
+            // The next image may be long enough to reach into the value rows that are being
+            // summed right now (only when chunk sizes differ a lot): then wait for the readers.
+            if (16u * (uint32_t)n16_next > val0)
+                __syncthreads();
+#pragma unroll
+            for (int j = 0; j < kPrefetchRegs; ++j) {
+                const int i = tid + j * kLdsThreads;
+                if (i < n16_next)
+                    lds_store_u4(16u * (uint32_t)i, pf[j]);
+            }
+            __syncthreads();
+        }
+        h = hn;
+    }
+    if (active && my_slot == 0 && r < d.n_rows)
+        d.row_score[r] = acc;
+}
+
+int launch_traverse_lds(const FamDesc *d_desc, int n_families, int total_blocks, bool dump,
+                        hipStream_t stream)
+{
+    static bool configured[16][2] = {};
+    int dev = 0;
+    FS_HIP(hipGetDevice(&dev));
+    const void *fn = dump ? (const void *)traverse_lds_kernel<true>
+                          : (const void *)traverse_lds_kernel<false>;
+    if (dev < 0 || dev >= 16 || !configured[dev][dump ? 1 : 0]) {
+        FS_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+        if (dev >= 0 && dev < 16)
+            configured[dev][dump ? 1 : 0] = true;
+    }
+    if (dump)
+        hipLaunchKernelGGL(traverse_lds_kernel<true>, dim3(total_blocks), dim3(kLdsThreads),
+                           kLdsBytes, stream, d_desc, n_families);
+    else
+        hipLaunchKernelGGL(traverse_lds_kernel<false>, dim3(total_blocks), dim3(kLdsThreads),
+                           kLdsBytes, stream, d_desc, n_families);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail_hip(e, "traverse_lds_kernel launch");
+    return FS_OK;
+}
+
+}  // namespace fs
