@@ -258,8 +258,8 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
     if (rc != FS_OK)
         return rc;
     FamDesc *h = (FamDesc *)slot->h_buf;
-    int64_t trav_blocks = 0, seg_blocks = 0, lds_blocks = 0;
-    bool dump = false;
+    int64_t trav_blocks = 0, seg_blocks = 0, lds_blocks[kLdsModes] = {0, 0};
+    bool dump[kLdsModes] = {false, false};
     size_t scratch_pos = 0;
     for (int f = 0; f < n_families; ++f) {
         const fs_family &a = fams[f];
@@ -284,7 +284,8 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         d.bias = a.model->bias;
         d.trav_block0 = (int32_t)trav_blocks;
         d.seg_block0 = (int32_t)seg_blocks;
-        d.lds_block0 = (int32_t)lds_blocks;
+        for (int md = 0; md < kLdsModes; ++md)
+            d.lds_block0[md] = (int32_t)lds_blocks[md];
         d.image = a.model->d_image;
         d.chunks = a.model->d_chunks;
         d.slot_ids = a.model->d_slot_ids;
@@ -292,21 +293,21 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         d.lds_tile0 = a.model->lds_tile0;
         d.lds_tiles = a.model->lds_tiles;
         d.compact = a.model->compact ? 1 : 0;
-        d.pad = 0;
         // Column-blocked features and a model that fits the LDS format take the LDS kernel;
         // everything else is walked from global memory.
         if (a.model->lds_ok && a.layout == FS_COLBLOCK64) {
             const int64_t tiles = (a.n_rows + 63) / 64;
-            lds_blocks += (tiles + a.model->lds_tiles - 1) / a.model->lds_tiles;
+            const int md = a.model->lds_mode;
+            lds_blocks[md] += (tiles + a.model->lds_tiles - 1) / a.model->lds_tiles;
             if (a.leaf_idx && a.n_rows > 0)
-                dump = true;
+                dump[md] = true;
         } else
         trav_blocks += (a.n_rows + kTravRowsPerBlock - 1) / kTravRowsPerBlock;
         seg_blocks += (a.n_programs + kSegProgsPerBlock - 1) / kSegProgsPerBlock;
         h[f] = d;
     }
     if (trav_blocks >= ((int64_t)1 << 31) || seg_blocks >= ((int64_t)1 << 31) ||
-        lds_blocks >= ((int64_t)1 << 31))
+        lds_blocks[0] >= ((int64_t)1 << 31) || lds_blocks[1] >= ((int64_t)1 << 31))
         return fail(FS_EUNSUPPORTED, "fs_score_families: too much work for one submission");
 
     FS_HIP(hipMemcpyAsync(slot->d_buf, slot->h_buf, sizeof(FamDesc) * (size_t)n_families,
@@ -314,9 +315,11 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
     slot->used = true;
     const FamDesc *d_desc = (const FamDesc *)slot->d_buf;
     rc = FS_OK;
-    if (lds_blocks > 0) {
+    for (int md = 0; md < kLdsModes && rc == FS_OK; ++md) {
+        if (lds_blocks[md] == 0)
+            continue;
         prof_start(kKernTraverse, stream);
-        rc = launch_traverse_lds(d_desc, n_families, (int)lds_blocks, dump, stream);
+        rc = launch_traverse_lds(d_desc, n_families, md, (int)lds_blocks[md], dump[md], stream);
         prof_stop(stream);
     }
     if (rc == FS_OK && trav_blocks > 0) {

@@ -47,8 +47,8 @@ struct ChunkHdr {
     uint32_t depth;       // split levels to walk (max over the chunk's trees)
     uint32_t first_tree;  // model-wide index of the chunk's first tree
     uint32_t slot_off;    // into the id map: entry [slot_off + (lds byte offset >> 2)]
-    uint32_t group;       // trees a wavefront walks at once in this chunk (1..8)
-    uint32_t pad;
+    uint32_t pad0;
+    uint32_t pad1;
 };
 
 // LDS map of the traversal kernel (bytes):
@@ -56,8 +56,14 @@ struct ChunkHdr {
 //   [tile0 - n_trees*tiles*256, tile0)     leaf values [tree in chunk][tile][lane] (fp32)
 //   [tile0, 160 KB)                        `tiles` feature tiles of (n_features+1)*256 bytes,
 //                                          tile0 = 160 KB - tiles * tile bytes
-constexpr int kLdsBytes = 160 * 1024;
-constexpr int kLdsWaves = 12;           // wavefronts per workgroup
+// Two workgroup shapes.  "small": half a compute unit's LDS, 6 wavefronts, one tile -- two
+// such workgroups share a compute unit, so one walks while the other is busy with barriers,
+// the ordered sum or the next chunk.  "big": the whole LDS, 12 wavefronts, 1-3 tiles -- for
+// models whose trees are too large to give a small workgroup enough trees per chunk.
+constexpr int kLdsModes = 2;
+constexpr int kLdsModeBytes[kLdsModes] = {80 * 1024, 160 * 1024};
+constexpr int kLdsModeWaves[kLdsModes] = {6, 12};
+constexpr int kLdsMaxWaves = 12;
 constexpr int kLdsMaxTiles = 3;         // 64-row tiles per workgroup (1, 2 or 3)
 constexpr int kMaxChunkBytes = 65536 - 16;
 constexpr int kMaxChunkTrees = 96;
@@ -78,6 +84,7 @@ struct fs_model {
     // LDS-staged format (absent if the model does not fit it)
     bool lds_ok;
     bool compact;          // perfect trees of one depth, 4-byte leaves
+    int32_t lds_mode;      // workgroup shape chosen for this model (index into kLdsMode*)
     int32_t lds_tiles;     // 64-row tiles per workgroup chosen for this model
     int32_t lds_tile0;     // LDS byte offset of the first feature tile
     int32_t n_chunks;
@@ -114,8 +121,7 @@ struct FamDesc {
     int32_t lds_tile0;
     int32_t lds_tiles;
     int32_t compact;
-    int32_t lds_block0;    // first block of the LDS traversal grid of this family
-    int32_t pad;
+    int32_t lds_block0[kLdsModes];   // first block of this family in each LDS launch
 };
 
 struct TopkDesc {
@@ -129,8 +135,8 @@ struct TopkDesc {
 // ---- launchers (each returns FS_OK or records an error) ---------------------------------------
 int launch_traverse_global(const FamDesc *d_desc, int n_families, int total_blocks,
                            hipStream_t stream);
-int launch_traverse_lds(const FamDesc *d_desc, int n_families, int total_blocks, bool dump,
-                        hipStream_t stream);
+int launch_traverse_lds(const FamDesc *d_desc, int n_families, int mode, int total_blocks,
+                        bool dump, hipStream_t stream);
 int launch_segsum(const FamDesc *d_desc, int n_families, int total_blocks, hipStream_t stream);
 int launch_topk(const TopkDesc *d_desc, int n_requests, int max_k, hipStream_t stream);
 int launch_pack_colblock64(const float *in, int64_t n_rows, int32_t n_features, float *out,

@@ -1,5 +1,6 @@
 // fs_model_create / fs_model_destroy: validation of the caller's ensemble and packing into
 // the two device formats (flat global-memory nodes; LDS-staged chunk images).
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -135,6 +136,14 @@ bool tree_is_perfect(const int32_t *sf, const int32_t *left, const int32_t *righ
     return *depth == d;
 }
 
+// Largest chunk image: node offsets are 16 bits, and the kernel stages the next chunk in
+// kPrefetchRegs 16-byte registers per thread.
+size_t chunk_image_limit(int mode)
+{
+    const size_t by_regs = (size_t)kLdsModeWaves[mode] * 64 * kPrefetchRegs * 16;
+    return by_regs < (size_t)kMaxChunkBytes ? by_regs : (size_t)kMaxChunkBytes;
+}
+
 void free_device(fs_model *m)
 {
     if (m->d_nodes) (void)hipFree(m->d_nodes);
@@ -258,35 +267,56 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                 sum_tree += b;
             }
             const size_t avg_tree = sum_tree / (size_t)n_trees;
-            // Pick the number of row tiles per workgroup.  More tiles mean fewer passes of the
-            // model through LDS, but less room for trees; what hides LDS latency is the number
-            // of independent walks in flight, tiles x trees resident, so that comes first.
-            int best_t = 0, best_score = -1;
+            // Pick the workgroup shape and the number of row tiles per workgroup.  More tiles
+            // mean fewer passes of the model through LDS, but less room for trees; what hides
+            // LDS latency is the number of independent walks in flight (tiles x trees
+            // resident), so that comes first.  The small shape is taken when it still gets 8
+            // or more trees into a chunk.
+            int best_t = 0, best_score = -1, best_mode = 0;
             size_t best_avail = 0;
-            for (int nt = all_trees ? kLdsMaxTiles : 0; nt >= 1; --nt) {
-                const long avail = (long)kLdsBytes - (long)nt * tile_bytes - 64;
-                const size_t per_tree_val = (size_t)nt * 256;
-                if (avail < (long)(max_tree + 16 + per_tree_val))
+            int forced_tiles = 0, forced_mode = 0;   // tuning aids: FS_TUNE_TILES, FS_TUNE_MODE
+            if (const char *e = getenv("FS_TUNE_TILES"))
+                forced_tiles = atoi(e);
+            if (const char *e = getenv("FS_TUNE_MODE"))
+                forced_mode = atoi(e);
+            for (int mode = 0; mode < kLdsModes && all_trees && best_t == 0; ++mode) {
+                if (forced_mode >= 1 && forced_mode <= kLdsModes && mode != forced_mode - 1)
                     continue;
-                size_t by_chunk = ((size_t)kMaxChunkBytes - 16) / (avg_tree + 4);
-                size_t by_avail = ((size_t)avail - 16) / (avg_tree + 4 + per_tree_val);
-                size_t per = by_chunk < by_avail ? by_chunk : by_avail;
-                if (per < 1) per = 1;
-                if (per > (size_t)kMaxChunkTrees) per = kMaxChunkTrees;
-                int score = nt * (int)per;
-                if (score > 24) score = 24;
-                if (score > best_score) {
-                    best_score = score;
-                    best_t = nt;
-                    best_avail = (size_t)avail;
+                const int max_tiles = mode == 0 ? 1 : kLdsMaxTiles;
+                for (int nt = max_tiles; nt >= 1; --nt) {
+                    if (mode == 1 && forced_tiles >= 1 && forced_tiles <= kLdsMaxTiles &&
+                        nt != forced_tiles)
+                        continue;
+                    const long avail = (long)kLdsModeBytes[mode] - (long)nt * tile_bytes - 64;
+                    const size_t per_tree_val = (size_t)nt * 256;
+                    if (avail < (long)(max_tree + 16 + per_tree_val))
+                        continue;
+                    const size_t max_img = chunk_image_limit(mode);
+                    if (max_img < max_tree + 16)
+                        continue;
+                    size_t by_chunk = (max_img - 16) / (avg_tree + 4);
+                    size_t by_avail = ((size_t)avail - 16) / (avg_tree + 4 + per_tree_val);
+                    size_t per = by_chunk < by_avail ? by_chunk : by_avail;
+                    if (per < 1) per = 1;
+                    if (per > (size_t)kMaxChunkTrees) per = kMaxChunkTrees;
+                    if (mode == 0 && per < 8 && forced_mode != 1)
+                        continue;
+                    int score = nt * (int)per;
+                    if (score > 24) score = 24;
+                    if (score > best_score) {
+                        best_score = score;
+                        best_t = nt;
+                        best_mode = mode;
+                        best_avail = (size_t)avail;
+                    }
                 }
             }
             if (best_t > 0) {
                 const size_t per_tree_val = (size_t)best_t * 256;
-                const int slots = kLdsWaves / best_t;
                 m->lds_ok = true;
                 m->compact = compact;
                 m->lds_tiles = best_t;
+                m->lds_mode = best_mode;
                 int t = 0;
                 while (t < n_trees) {
                     // how many trees fit: chunk image (table included) + their value rows
@@ -296,7 +326,7 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                         const size_t b = trees[(size_t)(t + cnt)].words.size() * 4;
                         const size_t table = ((size_t)(cnt + 1) * 4 + 7) & ~(size_t)7;
                         const size_t img = (table + body + b + 15) & ~(size_t)15;
-                        if (img > (size_t)kMaxChunkBytes ||
+                        if (img > chunk_image_limit(best_mode) ||
                             img + (size_t)(cnt + 1) * per_tree_val > best_avail)
                             break;
                         body += b;
@@ -312,10 +342,6 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                     h.n_trees = (uint32_t)cnt;
                     h.first_tree = (uint32_t)t;
                     h.slot_off = (uint32_t)slot_ids.size();
-                    // trees per walk: spread the chunk's trees evenly over the wavefronts that
-                    // share a tile, at most 8 at a time
-                    const int rounds = (cnt + 8 * slots - 1) / (8 * slots);
-                    h.group = (uint32_t)((cnt + slots * rounds - 1) / (slots * rounds));
                     image.resize(image.size() + bytes, 0);
                     slot_ids.resize(slot_ids.size() + bytes / 4, 0);
                     uint8_t *img = image.data() + h.byte_off;
@@ -341,7 +367,7 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                 }
                 m->n_chunks = (int32_t)chunks.size();
                 m->image_bytes = image.size();
-                m->lds_tile0 = kLdsBytes - best_t * tile_bytes;
+                m->lds_tile0 = kLdsModeBytes[best_mode] - best_t * tile_bytes;
             }
         }
 

@@ -4,7 +4,8 @@
 // per statement row, a walk through every tree and a sum of the reached leaves in tree
 // order.
 //
-// A workgroup of 12 wavefronts holds up to three 64-row feature tiles in LDS in the
+// A workgroup (6 wavefronts and one tile on half a compute unit's LDS, or 12 wavefronts and
+// up to three tiles on all of it) holds its 64-row feature tiles in LDS in the
 // column-blocked layout they have in HBM: row l of a tile is lane l, and column j sits at
 // j*256 + l*4, so a gather of 64 different features by 64 lanes touches 64 different
 // words in 64 different banks (no conflict whatever the features are).  The model streams
@@ -33,10 +34,17 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // LDS accesses by absolute byte address (the dynamic LDS block starts at address 0: the
 // kernel has no static LDS).
+// Pointers that arrive inside a descriptor are generic to the compiler; FS_GLOBAL / FS_CONST
+// tell it they are global memory (plain global loads that do not tie up the LDS counter) or
+// read-only uniform data (scalar loads).
 #if defined(__HIP_DEVICE_COMPILE__)
 #define FS_LDS_PTR(T, a) ((__attribute__((address_space(3))) T *)(uint32_t)(a))
+#define FS_GLOBAL(T, p) ((__attribute__((address_space(1))) T *)(uintptr_t)(p))
+#define FS_CONST(T, p) ((__attribute__((address_space(4))) const T *)(uintptr_t)(p))
 #else
 #define FS_LDS_PTR(T, a) ((T *)(uintptr_t)(a))   // host pass only parses the kernels
+#define FS_GLOBAL(T, p) ((T *)(uintptr_t)(p))
+#define FS_CONST(T, p) ((const T *)(uintptr_t)(p))
 #endif
 __device__ __forceinline__ u32x2 lds_u2(uint32_t a) { return *FS_LDS_PTR(const u32x2, a); }
 __device__ __forceinline__ float lds_f(uint32_t a) { return *FS_LDS_PTR(const float, a); }
@@ -90,9 +98,11 @@ __device__ __forceinline__ void walk_group(const uint32_t (&root)[K], int depth,
 // Trees [g, g+K) of the chunk: walk, park the leaf values, optionally report the leaf ids.
 template <int K, bool COMPACT, bool DUMP>
 __device__ __forceinline__ void walk_k(int g, int depth, uint32_t lane_base, uint32_t val_addr,
-                                       uint32_t val_stride, const uint16_t *slot_ids,
-                                       uint16_t *leaf_out)
+                                       uint32_t val_stride, const uint16_t *slot_ids_,
+                                       uint16_t *leaf_out_)
 {
+    auto slot_ids = FS_GLOBAL(const uint16_t, slot_ids_);
+    auto leaf_out = FS_GLOBAL(uint16_t, leaf_out_);
     uint32_t root[K], a[K];
     float v[K];
 #pragma unroll
@@ -103,7 +113,7 @@ __device__ __forceinline__ void walk_k(int g, int depth, uint32_t lane_base, uin
     for (int k = 0; k < K; ++k)
         lds_store_f(val_addr + (uint32_t)(g + k) * val_stride, v[k]);
     if (DUMP) {
-        if (leaf_out) {
+        if (leaf_out_) {
 #pragma unroll
             for (int k = 0; k < K; ++k)
                 leaf_out[g + k] = slot_ids[a[k] >> 2];
@@ -129,16 +139,16 @@ __device__ __forceinline__ void walk_n(int count, int g, int depth, uint32_t lan
     }
 }
 
-constexpr int kLdsThreads = 64 * kLdsWaves;
-
 template <bool DUMP>
-__global__ void __launch_bounds__(kLdsThreads)
-traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families)
+__global__ void __launch_bounds__(64 * kLdsMaxWaves)
+traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
 {
+    const int kLdsThreads = blockDim.x;
+    const int kLdsWaves = kLdsThreads >> 6;
     int lo = 0, hi = n_families - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
-        if (descs[mid].lds_block0 <= (int)blockIdx.x)
+        if (descs[mid].lds_block0[mode] <= (int)blockIdx.x)
             lo = mid;
         else
             hi = mid - 1;
@@ -150,7 +160,7 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families)
     const int S = kLdsWaves / T;                // wavefronts sharing a tile
     const int my_tile = wave % T, my_slot = wave / T;
     const int n_tiles = (d.n_rows + 63) >> 6;
-    const int tile_first = (blockIdx.x - d.lds_block0) * T;
+    const int tile_first = (blockIdx.x - d.lds_block0[mode]) * T;
     const int tiles_here = min(T, n_tiles - tile_first);
     const bool active = my_tile < tiles_here;
     const int F = d.n_features;
@@ -158,19 +168,51 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families)
     const uint32_t tile0 = (uint32_t)d.lds_tile0;
     const uint32_t lane_base = tile0 + (uint32_t)my_tile * tile_bytes + 4u * (uint32_t)lane;
 
+    // ---- first chunk: global -> registers (lands while the tiles are being fetched) ----
+    // Loads are unconditional with clamped indices (no branches between them, so they all go
+    // out back to back); only the LDS writes are predicated.
+    u32x4 pf[kPrefetchRegs];
+    ChunkHdr h = *FS_CONST(ChunkHdr, d.chunks);
+    {
+        auto src = FS_GLOBAL(const u32x4, d.image + h.byte_off);
+        const int n16 = (int)(h.bytes >> 4);
+#pragma unroll
+        for (int j = 0; j < kPrefetchRegs; ++j)
+            pf[j] = src[min(tid + j * kLdsThreads, n16 - 1)];
+    }
     // ---- feature tiles: consecutive tiles are one contiguous run in HBM ----
     {
-        const u32x4 *src = (const u32x4 *)(d.features + (int64_t)tile_first * F * 64);
+        auto src = FS_GLOBAL(const u32x4, d.features + (int64_t)tile_first * F * 64);
         const int per_tile = F * 16;                       // 16-byte pieces per tile
         const int n16 = tiles_here * per_tile;
-        for (int i = tid; i < n16; i += kLdsThreads) {
-            const int t = i / per_tile, j = i - t * per_tile;
-            lds_store_u4(tile0 + (uint32_t)t * tile_bytes + 16u * (uint32_t)j, src[i]);
+        for (int base = tid; base < n16; base += 4 * kLdsThreads) {
+            u32x4 t4[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                t4[q] = src[min(base + q * kLdsThreads, n16 - 1)];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int i = base + q * kLdsThreads;
+                if (i < n16) {
+                    const int t = i / per_tile, j = i - t * per_tile;
+                    lds_store_u4(tile0 + (uint32_t)t * tile_bytes + 16u * (uint32_t)j, t4[q]);
+                }
+            }
         }
         if (tid < 64 * tiles_here)
             lds_store_f(tile0 + (uint32_t)(tid >> 6) * tile_bytes + (uint32_t)F * 256u +
                             4u * (uint32_t)(tid & 63), __builtin_nanf(""));
     }
+    {
+        const int n16 = (int)(h.bytes >> 4);
+#pragma unroll
+        for (int j = 0; j < kPrefetchRegs; ++j) {
+            const int i = tid + j * kLdsThreads;
+            if (i < n16)
+                lds_store_u4(16u * (uint32_t)i, pf[j]);
+        }
+    }
+    __syncthreads();
 
     const int r = (tile_first + my_tile) * 64 + lane;
     float acc = d.bias;
@@ -183,51 +225,32 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families)
     const int n_chunks = d.n_chunks;
     const uint32_t val_stride = (uint32_t)T * 256u;        // bytes between trees' value rows
 
-    // ---- first chunk ----
-    u32x4 pf[kPrefetchRegs];
-    ChunkHdr h = d.chunks[0];
-    {
-        const u32x4 *src = (const u32x4 *)(d.image + h.byte_off);
-        const int n16 = (int)(h.bytes >> 4);
-#pragma unroll
-        for (int j = 0; j < kPrefetchRegs; ++j) {
-            const int i = tid + j * kLdsThreads;
-            if (i < n16)
-                pf[j] = src[i];
-        }
-#pragma unroll
-        for (int j = 0; j < kPrefetchRegs; ++j) {
-            const int i = tid + j * kLdsThreads;
-            if (i < n16)
-                lds_store_u4(16u * (uint32_t)i, pf[j]);
-        }
-    }
-    __syncthreads();
-
     for (int c = 0; c < n_chunks; ++c) {
         ChunkHdr hn = h;
         int n16_next = 0;
         if (c + 1 < n_chunks) {                            // next chunk: global -> registers
-            hn = d.chunks[c + 1];
-            const u32x4 *src = (const u32x4 *)(d.image + hn.byte_off);
+            hn = *FS_CONST(ChunkHdr, d.chunks + c + 1);
+            auto src = FS_GLOBAL(const u32x4, d.image + hn.byte_off);
             n16_next = (int)(hn.bytes >> 4);
 #pragma unroll
-            for (int j = 0; j < kPrefetchRegs; ++j) {
-                const int i = tid + j * kLdsThreads;
-                if (i < n16_next)
-                    pf[j] = src[i];
-            }
+            for (int j = 0; j < kPrefetchRegs; ++j)
+                pf[j] = src[min(tid + j * kLdsThreads, n16_next - 1)];
         }
         const int n = uniform((int)h.n_trees);
         const int depth = uniform((int)h.depth);
-        const int group = uniform((int)h.group);
         const uint32_t val0 = tile0 - (uint32_t)n * val_stride;   // packing keeps it above the image
         if (active) {
             const uint32_t val_addr = val0 + (uint32_t)my_tile * 256u + 4u * (uint32_t)lane;
             const uint16_t *ids = d.slot_ids + h.slot_off;
             uint16_t *leaf_out = leaf_row ? leaf_row + h.first_tree : nullptr;
-            for (int g = my_slot * group; g < n; g += S * group) {
-                const int count = min(group, n - g);
+            // The chunk's trees are dealt out in `n_groups` runs of consecutive trees whose
+            // sizes differ by at most one (sizes <= 8); wavefront s of the tile takes runs
+            // s, s+S, ...
+            const int n_groups = S * ((n + 8 * S - 1) / (8 * S));
+            const int base = n / n_groups, rem = n - base * n_groups;
+            for (int j = my_slot; j < n_groups; j += S) {
+                const int g = j * base + min(j, rem);
+                const int count = base + (j < rem ? 1 : 0);
                 if (compact)
                     walk_n<true, DUMP>(count, g, depth, lane_base, val_addr, val_stride, ids, leaf_out);
                 else
@@ -237,7 +260,18 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families)
         __syncthreads();       // every walk of this chunk is done and its values are parked
         if (active && my_slot == 0) {
             uint32_t va = val0 + (uint32_t)my_tile * 256u + 4u * (uint32_t)lane;
-            for (int t = 0; t < n; ++t) {
+            int t = 0;
+            for (; t + 8 <= n; t += 8) {                   // loads first, then the ordered adds
+                float v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    v[k] = lds_f(va + (uint32_t)k * val_stride);
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    acc = acc + v[k];
+                va += 8u * val_stride;
+            }
+            for (; t < n; ++t) {
                 acc = acc + lds_f(va);
                 va += val_stride;
             }
@@ -258,28 +292,31 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families)
         h = hn;
     }
     if (active && my_slot == 0 && r < d.n_rows)
-        d.row_score[r] = acc;
+        FS_GLOBAL(float, d.row_score)[r] = acc;
 }
 
-int launch_traverse_lds(const FamDesc *d_desc, int n_families, int total_blocks, bool dump,
-                        hipStream_t stream)
+int launch_traverse_lds(const FamDesc *d_desc, int n_families, int mode, int total_blocks,
+                        bool dump, hipStream_t stream)
 {
+    const int kLdsBytes = kLdsModeBytes[mode];
+    const int kLdsThreads = 64 * kLdsModeWaves[mode];
     static bool configured[16][2] = {};
     int dev = 0;
     FS_HIP(hipGetDevice(&dev));
     const void *fn = dump ? (const void *)traverse_lds_kernel<true>
                           : (const void *)traverse_lds_kernel<false>;
     if (dev < 0 || dev >= 16 || !configured[dev][dump ? 1 : 0]) {
-        FS_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+        FS_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   kLdsModeBytes[kLdsModes - 1]));
         if (dev >= 0 && dev < 16)
             configured[dev][dump ? 1 : 0] = true;
     }
     if (dump)
         hipLaunchKernelGGL(traverse_lds_kernel<true>, dim3(total_blocks), dim3(kLdsThreads),
-                           kLdsBytes, stream, d_desc, n_families);
+                           kLdsBytes, stream, d_desc, n_families, mode);
     else
         hipLaunchKernelGGL(traverse_lds_kernel<false>, dim3(total_blocks), dim3(kLdsThreads),
-                           kLdsBytes, stream, d_desc, n_families);
+                           kLdsBytes, stream, d_desc, n_families, mode);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return fail_hip(e, "traverse_lds_kernel launch");
