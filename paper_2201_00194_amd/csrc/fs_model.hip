@@ -1,5 +1,6 @@
 // fs_model_create / fs_model_destroy: validation of the caller's ensemble and packing into
 // the two device formats (flat global-memory nodes; LDS-staged chunk images).
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -279,7 +280,11 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                 forced_tiles = atoi(e);
             if (const char *e = getenv("FS_TUNE_MODE"))
                 forced_mode = atoi(e);
-            for (int mode = 0; mode < kLdsModes && all_trees && best_t == 0; ++mode) {
+            for (int mode = kLdsModes - 1; mode >= 0 && all_trees && best_t == 0; --mode) {
+                // The half-LDS shape (two workgroups per compute unit) measured no faster on
+                // any workload and doubles the model traffic from L2: tuning aid only.
+                if (mode == 0 && forced_mode != 1)
+                    continue;
                 if (forced_mode >= 1 && forced_mode <= kLdsModes && mode != forced_mode - 1)
                     continue;
                 const int max_tiles = mode == 0 ? 1 : kLdsMaxTiles;
@@ -302,7 +307,8 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                     if (mode == 0 && per < 8 && forced_mode != 1)
                         continue;
                     int score = nt * (int)per;
-                    if (score > 24) score = 24;
+                    if (score > 64) score = 64;   // measured: beyond ~5 trees per wavefront more
+                                                  // tiles win, below it more trees per chunk do
                     if (score > best_score) {
                         best_score = score;
                         best_t = nt;
@@ -311,6 +317,10 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                     }
                 }
             }
+            if (best_t > 0 && getenv("FS_TUNE_VERBOSE"))
+                fprintf(stderr, "fs_model_create: mode=%d tiles=%d avail=%zu avg_tree=%zu "
+                        "max_tree=%zu compact=%d\n", best_mode, best_t, best_avail, avg_tree,
+                        max_tree, (int)compact);
             if (best_t > 0) {
                 const size_t per_tree_val = (size_t)best_t * 256;
                 m->lds_ok = true;

@@ -306,6 +306,13 @@ int launch_traverse_lds(const FamDesc *d_desc, int n_families, int mode, int tot
     const void *fn = dump ? (const void *)traverse_lds_kernel<true>
                           : (const void *)traverse_lds_kernel<false>;
     if (dev < 0 || dev >= 16 || !configured[dev][dump ? 1 : 0]) {
+        // The kernel addresses LDS absolutely from 0, so it must own all of it: no static LDS
+        // (nothing the compiler may have moved there either).
+        hipFuncAttributes attr;
+        FS_HIP(hipFuncGetAttributes(&attr, fn));
+        if (attr.sharedSizeBytes != 0)
+            return fail(FS_EDEVICE, "traverse_lds_kernel was built with %zu bytes of static LDS",
+                        (size_t)attr.sharedSizeBytes);
         FS_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                    kLdsModeBytes[kLdsModes - 1]));
         if (dev >= 0 && dev < 16)
