@@ -58,7 +58,7 @@ def source_digest() -> str:
 def recorded_traffic(config: int):
     """HBM bytes per launch of the traversal kernel from the committed counter summary, or
     None if there is none for this workload or the kernels changed since it was taken."""
-    path = os.path.join(ROOT, "profiles", "traverse_hbm_traffic.json")
+    path = os.path.join(ROOT, "profiles", "traverse_hbm_traffic.txt")
     try:
         rec = json.load(open(path))
     except (OSError, ValueError):
