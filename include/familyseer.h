@@ -178,7 +178,9 @@ enum { FS_KERNEL_TRAVERSE = 0,        /* LDS-staged traversal (the hot kernel)  
        FS_KERNEL_SEGSUM = 1, FS_KERNEL_TOPK = 2, FS_KERNEL_PACK = 3,
        FS_KERNEL_TRAVERSE_GLOBAL = 4, /* traversal from global memory (models/layouts that
                                          the LDS kernel does not take)                       */
-       FS_KERNEL_CLASSES = 5 };
+       FS_KERNEL_RANK_CODE = 5,       /* features -> 16-bit ranks (deep perfect-tree models)  */
+       FS_KERNEL_TRAVERSE_RANK = 6,   /* LDS-staged traversal over rank-coded features        */
+       FS_KERNEL_CLASSES = 7 };
 
 /*
  * Between fs_profile_begin and fs_profile_end the library brackets every kernel group it

@@ -248,6 +248,8 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
                         (long long)a.n_rows);
         if (!a.row_score)
             scratch_floats += (size_t)a.n_rows;
+        if (a.model->rank_ok && a.layout == FS_COLBLOCK64)   // u16 rank tiles, in float units
+            scratch_floats += (size_t)((a.n_rows + 63) / 64) * 32 * (size_t)a.model->n_features + 4;
     }
     rc = ensure_scratch(ctx, scratch_floats);
     if (rc != FS_OK)
@@ -259,6 +261,8 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         return rc;
     FamDesc *h = (FamDesc *)slot->h_buf;
     int64_t trav_blocks = 0, seg_blocks = 0, lds_blocks[kLdsModes] = {0, 0};
+    int64_t rk_blocks = 0, bin_blocks = 0;
+    bool rk_dump = false;
     bool dump[kLdsModes] = {false, false};
     size_t scratch_pos = 0;
     for (int f = 0; f < n_families; ++f) {
@@ -293,9 +297,45 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         d.lds_tile0 = a.model->lds_tile0;
         d.lds_tiles = a.model->lds_tiles;
         d.compact = a.model->compact ? 1 : 0;
-        // Column-blocked features and a model that fits the LDS format take the LDS kernel;
-        // everything else is walked from global memory.
-        if (a.model->lds_ok && a.layout == FS_COLBLOCK64) {
+        d.rk_nodes = a.model->d_rk_nodes;
+        d.rk_ids = a.model->d_rk_ids;
+        d.cuts = a.model->d_cuts;
+        d.ranks = nullptr;
+        d.rk_depth = a.model->rk_depth;
+        d.rk_tiles = a.model->rk_tiles;
+        d.rk_trees_per_chunk = a.model->rk_trees_per_chunk;
+        d.rk_tree_bytes = a.model->rk_tree_bytes;
+        d.rk_tile0 = a.model->rk_tile0;
+        d.rk_block0 = (int32_t)rk_blocks;
+        d.bin_block0 = (int32_t)bin_blocks;
+        d.bin_groups = 1;
+        d.bin_feats_per_group = a.model->n_features;
+        d.bin_tiles_per_block = kBinTilesPerBlock;
+        d.cut_bits = a.model->cut_bits;
+        d.pad = 0;
+        // Column-blocked features: deep perfect-tree models are rank-coded first and walked by
+        // the rank kernel, other models that fit the LDS format take the LDS kernel; everything
+        // else is walked from global memory.
+        if (a.model->rank_ok && a.layout == FS_COLBLOCK64) {
+            const int64_t tiles = (a.n_rows + 63) / 64;
+            scratch_pos = (scratch_pos + 3) & ~(size_t)3;            // 16-byte aligned tiles
+            d.ranks = (uint16_t *)(ctx->scratch + scratch_pos);
+            scratch_pos += (size_t)tiles * 32 * (size_t)a.model->n_features;
+            const int len = 1 << a.model->cut_bits;
+            int per_group = kBinTableBytes / 4 / len;
+            if (per_group > a.model->n_features) per_group = a.model->n_features;
+            d.bin_feats_per_group = per_group;                      // >= 1 by model packing
+            d.bin_groups = (a.model->n_features + per_group - 1) / per_group;
+            // enough workgroups to fill the chip even for a small family
+            int64_t tpb = tiles * d.bin_groups / 2048;
+            if (tpb < 2) tpb = 2;
+            if (tpb > kBinTilesPerBlock) tpb = kBinTilesPerBlock;
+            d.bin_tiles_per_block = (int32_t)tpb;
+            bin_blocks += (int64_t)d.bin_groups * ((tiles + tpb - 1) / tpb);
+            rk_blocks += (tiles + a.model->rk_tiles - 1) / a.model->rk_tiles;
+            if (a.leaf_idx && a.n_rows > 0)
+                rk_dump = true;
+        } else if (a.model->lds_ok && a.layout == FS_COLBLOCK64) {
             const int64_t tiles = (a.n_rows + 63) / 64;
             const int md = a.model->lds_mode;
             lds_blocks[md] += (tiles + a.model->lds_tiles - 1) / a.model->lds_tiles;
@@ -307,7 +347,8 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         h[f] = d;
     }
     if (trav_blocks >= ((int64_t)1 << 31) || seg_blocks >= ((int64_t)1 << 31) ||
-        lds_blocks[0] >= ((int64_t)1 << 31) || lds_blocks[1] >= ((int64_t)1 << 31))
+        lds_blocks[0] >= ((int64_t)1 << 31) || lds_blocks[1] >= ((int64_t)1 << 31) ||
+        rk_blocks >= ((int64_t)1 << 31) || bin_blocks >= ((int64_t)1 << 31))
         return fail(FS_EUNSUPPORTED, "fs_score_families: too much work for one submission");
 
     FS_HIP(hipMemcpyAsync(slot->d_buf, slot->h_buf, sizeof(FamDesc) * (size_t)n_families,
@@ -320,6 +361,16 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
             continue;
         prof_start(kKernTraverse, stream);
         rc = launch_traverse_lds(d_desc, n_families, md, (int)lds_blocks[md], dump[md], stream);
+        prof_stop(stream);
+    }
+    if (rc == FS_OK && bin_blocks > 0) {
+        prof_start(kKernRankCode, stream);
+        rc = launch_rank_code(d_desc, n_families, (int)bin_blocks, stream);
+        prof_stop(stream);
+    }
+    if (rc == FS_OK && rk_blocks > 0) {
+        prof_start(kKernTraverseRank, stream);
+        rc = launch_traverse_rank(d_desc, n_families, (int)rk_blocks, rk_dump, stream);
         prof_stop(stream);
     }
     if (rc == FS_OK && trav_blocks > 0) {

@@ -92,6 +92,19 @@ struct fs_model {
     fs::ChunkHdr *d_chunks;
     uint16_t *d_slot_ids;  // caller's local node id per 4-byte slot (leaves only meaningful)
     size_t image_bytes;
+    // Rank-coded format (deep perfect trees): features become 16-bit ranks among the model's
+    // own thresholds of that feature, nodes shrink to 4 bytes (see fs_traverse_rank.hip)
+    bool rank_ok;
+    int32_t rk_depth;          // common depth of the trees
+    int32_t rk_tiles;          // 64-row tiles per workgroup
+    int32_t rk_trees_per_chunk;
+    int32_t rk_tree_bytes;     // 4 * (2^(depth+1) - 1)
+    int32_t rk_tile0;          // LDS byte offset of the first (u16) feature tile
+    uint32_t *d_rk_nodes;      // [n_trees][2^(depth+1) - 1] heap order: splits then leaf values
+    uint16_t *d_rk_ids;        // same shape: caller's local node id
+    float *d_cuts;             // [n_features][2^cut_bits]: the feature's sorted distinct
+                               // thresholds, NaN-padded, as a breadth-first search tree
+    int32_t cut_bits;
 };
 
 namespace fs {
@@ -122,6 +135,19 @@ struct FamDesc {
     int32_t lds_tiles;
     int32_t compact;
     int32_t lds_block0[kLdsModes];   // first block of this family in each LDS launch
+    // rank-coded traversal
+    const uint32_t *rk_nodes;
+    const uint16_t *rk_ids;
+    const float *cuts;
+    uint16_t *ranks;                 // scratch: rank-coded feature tiles [tile][feature][64]
+    int32_t rk_depth, rk_tiles, rk_trees_per_chunk, rk_tree_bytes, rk_tile0;
+    int32_t rk_block0;               // first block of the rank traversal grid
+    int32_t bin_block0;              // first block of the rank-coding grid
+    int32_t bin_groups;              // feature groups of this family in the rank-coding grid
+    int32_t bin_feats_per_group;
+    int32_t bin_tiles_per_block;
+    int32_t cut_bits;                // threshold tables are padded to 2^cut_bits entries
+    int32_t pad;
 };
 
 struct TopkDesc {
@@ -137,6 +163,9 @@ int launch_traverse_global(const FamDesc *d_desc, int n_families, int total_bloc
                            hipStream_t stream);
 int launch_traverse_lds(const FamDesc *d_desc, int n_families, int mode, int total_blocks,
                         bool dump, hipStream_t stream);
+int launch_rank_code(const FamDesc *d_desc, int n_families, int total_blocks, hipStream_t stream);
+int launch_traverse_rank(const FamDesc *d_desc, int n_families, int total_blocks, bool dump,
+                         hipStream_t stream);
 int launch_segsum(const FamDesc *d_desc, int n_families, int total_blocks, hipStream_t stream);
 int launch_topk(const TopkDesc *d_desc, int n_requests, int max_k, hipStream_t stream);
 int launch_pack_colblock64(const float *in, int64_t n_rows, int32_t n_features, float *out,
@@ -144,11 +173,19 @@ int launch_pack_colblock64(const float *in, int64_t n_rows, int32_t n_features, 
 
 // ---- optional per-kernel timing (fs_profile_begin / fs_profile_end) ----------------------------
 enum KernelClass { kKernTraverse = 0, kKernSegsum = 1, kKernTopk = 2, kKernPack = 3,
-                   kKernTraverseGlobal = 4, kKernClasses = 5 };
+                   kKernTraverseGlobal = 4, kKernRankCode = 5, kKernTraverseRank = 6,
+                   kKernClasses = 7 };
 // Records an event pair around the launches made between prof_start and prof_stop when
 // profiling is on; no-ops otherwise.  Both run under the API mutex.
 void prof_start(int kernel_class, hipStream_t stream);
 void prof_stop(hipStream_t stream);
+
+// rank-coding kernel: most tiles handled by one workgroup, LDS bytes for threshold tables
+constexpr int kBinTilesPerBlock = 256;
+constexpr int kBinTableBytes = 64 * 1024;
+constexpr int kRankWaves = 12;
+constexpr int kRankLdsBytes = 160 * 1024;
+constexpr int kRankPrefetchRegs = 6;     // 16-byte registers per thread for the next chunk
 
 constexpr int kTravRowsPerBlock = 256;   // rows per block of the global-memory traversal
 constexpr int kSegProgsPerBlock = 256;   // programs per block of the segmented sum

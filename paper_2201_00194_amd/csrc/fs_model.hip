@@ -1,5 +1,6 @@
 // fs_model_create / fs_model_destroy: validation of the caller's ensemble and packing into
 // the two device formats (flat global-memory nodes; LDS-staged chunk images).
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -145,6 +146,116 @@ size_t chunk_image_limit(int mode)
     return by_regs < (size_t)kMaxChunkBytes ? by_regs : (size_t)kMaxChunkBytes;
 }
 
+// Rank-coded image of a model of perfect trees of one depth (see fs_rank.hip): per feature the
+// sorted distinct thresholds; per tree 2^(depth+1) words, word i = heap node i (1-based),
+// splits as rank << 16 | feature*128, leaves as value bits; plus the caller's node id per word.
+void build_rank_format(fs_model *m, int n_features, int n_trees, int depth, const int32_t *tree_off,
+                       const int32_t *sf, const float *thr, const int32_t *left,
+                       const int32_t *right, const float *val, std::vector<uint32_t> *nodes,
+                       std::vector<uint16_t> *ids, std::vector<float> *cuts)
+{
+    // thresholds per feature: -0 joins +0, NaN thresholds never send anything left (rank 0)
+    std::vector<std::vector<float>> per((size_t)n_features);
+    const int64_t n_nodes = tree_off[n_trees];
+    for (int64_t g = 0; g < n_nodes; ++g)
+        if (sf[g] >= 0 && thr[g] == thr[g])
+            per[(size_t)sf[g]].push_back(thr[g] + 0.0f);
+    size_t max_cuts = 0;
+    for (int f = 0; f < n_features; ++f) {
+        std::vector<float> &v = per[(size_t)f];
+        std::sort(v.begin(), v.end());
+        v.erase(std::unique(v.begin(), v.end()), v.end());
+        if (v.size() > max_cuts) max_cuts = v.size();
+    }
+    int bits = 2;                                         // stride of 2^bits entries per feature
+    while ((((size_t)1 << bits) - 1) < max_cuts)
+        ++bits;
+    const size_t len = (size_t)1 << bits;
+    if (bits > 15 || len * 4 > (size_t)kBinTableBytes)
+        return;                                           // ranks must fit 16 bits and LDS
+    // per feature: the sorted keys, padded with NaN to 2^bits - 1, as an implicit search tree in
+    // breadth-first order: node 2^l + k (k-th of level l) holds sorted key (2k+1)*2^(bits-l-1) - 1
+    cuts->assign(len * (size_t)n_features, __builtin_nanf(""));
+    for (int f = 0; f < n_features; ++f) {
+        const std::vector<float> &v = per[(size_t)f];
+        float *tab = cuts->data() + (size_t)f * len;
+        for (int l = 0; l < bits; ++l)
+            for (size_t k = 0; k < ((size_t)1 << l); ++k) {
+                const size_t sorted_idx = (2 * k + 1) * ((size_t)1 << (bits - l - 1)) - 1;
+                if (sorted_idx < v.size())
+                    tab[((size_t)1 << l) + k] = v[sorted_idx];
+            }
+    }
+
+    const size_t words = (size_t)2 << depth;              // per tree, word 0 unused
+    nodes->assign(words * (size_t)n_trees, 0u);
+    ids->assign(words * (size_t)n_trees, 0);
+    std::vector<int32_t> at(words);                       // caller's node at heap position i
+    for (int t = 0; t < n_trees; ++t) {
+        const int32_t o = tree_off[t];
+        at[1] = 0;
+        for (size_t i = 1; i < words; ++i) {
+            const int32_t n = at[i];
+            uint32_t w;
+            if (sf[o + n] >= 0) {
+                at[2 * i] = left[o + n];
+                at[2 * i + 1] = right[o + n];
+                const float th = thr[o + n];
+                uint32_t rank = 0;
+                if (th == th) {
+                    const std::vector<float> &v = per[(size_t)sf[o + n]];
+                    rank = 1u + (uint32_t)(std::lower_bound(v.begin(), v.end(), th + 0.0f) - v.begin());
+                }
+                w = (rank << 16) | ((uint32_t)sf[o + n] * 128u);
+            } else {
+                memcpy(&w, &val[o + n], 4);
+            }
+            (*nodes)[(size_t)t * words + i] = w;
+            (*ids)[(size_t)t * words + i] = (uint16_t)n;
+        }
+    }
+
+    // tiles per workgroup (must divide the wavefront count): most (tiles x trees per chunk)
+    const size_t tree_bytes = words * 4, tile_bytes = (size_t)n_features * 128;
+    const size_t reg_limit = (size_t)kRankPrefetchRegs * 64 * kRankWaves * 16;
+    int best_t = 0, best_per = 0, best_score = -1;
+    int forced = 0;
+    if (const char *e = getenv("FS_TUNE_RANK_TILES"))
+        forced = atoi(e);
+    const int choices[] = {6, 4, 3, 2, 1};
+    for (int nt : choices) {
+        if (forced > 0 && nt != forced)
+            continue;
+        const long avail = (long)kRankLdsBytes - (long)nt * (long)tile_bytes - 64;
+        if (avail < (long)(tree_bytes + (size_t)nt * 256))
+            continue;
+        size_t per_c = (size_t)avail / (tree_bytes + (size_t)nt * 256);
+        if (per_c > reg_limit / tree_bytes) per_c = reg_limit / tree_bytes;
+        if (per_c > (size_t)kMaxChunkTrees) per_c = kMaxChunkTrees;
+        if (per_c < 1)
+            continue;
+        int score = nt * (int)per_c;
+        if (score > 64) score = 64;
+        if (score > best_score) {
+            best_score = score;
+            best_t = nt;
+            best_per = (int)per_c;
+        }
+    }
+    if (best_t == 0)
+        return;
+    m->rank_ok = true;
+    m->rk_depth = depth;
+    m->rk_tiles = best_t;
+    m->rk_trees_per_chunk = best_per;
+    m->rk_tree_bytes = (int32_t)tree_bytes;
+    m->rk_tile0 = kRankLdsBytes - best_t * (int32_t)tile_bytes;
+    m->cut_bits = bits;
+    if (getenv("FS_TUNE_VERBOSE"))
+        fprintf(stderr, "fs_model_create: rank-coded depth=%d tiles=%d trees/chunk=%d max_cuts=%zu\n",
+                depth, best_t, best_per, max_cuts);
+}
+
 void free_device(fs_model *m)
 {
     if (m->d_nodes) (void)hipFree(m->d_nodes);
@@ -152,6 +263,9 @@ void free_device(fs_model *m)
     if (m->d_image) (void)hipFree(m->d_image);
     if (m->d_chunks) (void)hipFree(m->d_chunks);
     if (m->d_slot_ids) (void)hipFree(m->d_slot_ids);
+    if (m->d_rk_nodes) (void)hipFree(m->d_rk_nodes);
+    if (m->d_rk_ids) (void)hipFree(m->d_rk_ids);
+    if (m->d_cuts) (void)hipFree(m->d_cuts);
 }
 
 template <typename T>
@@ -381,6 +495,27 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
             }
         }
 
+        // ---- rank-coded format: deep perfect trees ----
+        std::vector<uint32_t> rk_nodes;
+        std::vector<uint16_t> rk_ids;
+        std::vector<float> cuts;
+        {
+            int want = -1;                      // tuning aid: FS_TUNE_RANK=0 never, 1 whenever possible
+            if (const char *e = getenv("FS_TUNE_RANK"))
+                want = atoi(e);
+            int depth = -1;
+            bool perfect = n_trees > 0 && n_features <= 511 && want != 0;
+            for (int t = 0; t < n_trees && perfect; ++t) {
+                const int32_t o = tree_off[t];
+                perfect = tree_is_perfect(split_feature + o, left + o, right + o, tree_off[t + 1] - o,
+                                          &depth);
+            }
+            // worth it when the fp32 format gets fewer than ~10 trees into a chunk
+            if (perfect && (want == 1 || depth >= 9) && depth <= 12)
+                build_rank_format(m, n_features, n_trees, depth, tree_off, split_feature, threshold,
+                                  left, right, value, &rk_nodes, &rk_ids, &cuts);
+        }
+
         hipError_t e = hipGetDevice(&m->device);
         if (e == hipSuccess) {
             std::vector<int32_t> toff(tree_off, tree_off + n_trees + 1);
@@ -390,6 +525,11 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
         if (e == hipSuccess) e = upload(&m->d_image, image);
         if (e == hipSuccess) e = upload(&m->d_chunks, chunks);
         if (e == hipSuccess) e = upload(&m->d_slot_ids, slot_ids);
+        if (e == hipSuccess && m->rank_ok) {
+            e = upload(&m->d_rk_nodes, rk_nodes);
+            if (e == hipSuccess) e = upload(&m->d_rk_ids, rk_ids);
+            if (e == hipSuccess) e = upload(&m->d_cuts, cuts);
+        }
         if (e != hipSuccess) {
             free_device(m);
             delete m;

@@ -243,3 +243,38 @@ def test_errors_are_reported_not_raised_as_faults(api):
     # the library still works afterwards
     api.fs_score_families([d.family()])
     torch.cuda.synchronize()
+
+
+def test_rank_coded_path_special_values_and_shallow_trees(api, oracle, monkeypatch):
+    """Deep perfect-tree models are walked over 16-bit ranks of the features among the model's
+    own thresholds; the leaves must be the same as over the fp32 values, also for NaN, inf,
+    signed zeros and denormals in features and thresholds.  Forced here for shallow trees too."""
+    monkeypatch.setenv("FS_TUNE_RANK", "1")
+    fams = []
+    for i, (P, stm, T, dep, k) in enumerate([(700, (1, 5), 60, 10, 100), (300, (2, 2), 25, 9, 40),
+                                              (500, (1, 9), 70, 6, 64), (90, (3, 3), 10, 1, 8),
+                                              (65, (1, 2), 33, 11, 70)]):
+        fam = W.make_small_family(seed=200 + i, n_programs=P, stmts=stm, n_trees=T, depth=dep, k=k,
+                                  bias=[0.0, 0.25, -1.0, 0.0, 2.0][i])
+        rng = np.random.default_rng(300 + i)
+        X = fam.features
+        for val in (np.nan, np.inf, -np.inf, -0.0, 1e-42, -1e-42, -0.5):
+            r = rng.integers(0, X.shape[0], 150)
+            c = rng.integers(0, X.shape[1], 150)
+            X[r, c] = val
+        internal = np.flatnonzero(fam.model.split_feature >= 0)
+        pick = rng.choice(internal, min(40, internal.shape[0]), replace=False)
+        q = max(1, pick.shape[0] // 5)
+        fam.model.threshold[pick[:q]] = np.inf
+        fam.model.threshold[pick[q:2 * q]] = -0.0
+        fam.model.threshold[pick[2 * q:3 * q]] = np.nan
+        fam.model.threshold[pick[3 * q:4 * q]] = 1e-42
+        fam.model.threshold[pick[4 * q:]] = -np.inf
+        fams.append(fam)
+    devs = run_families(api, fams, api.FS_COLBLOCK64)
+    for f, d in zip(fams, devs):
+        check_family(oracle, f, d)
+    # same families without the optional outputs (the timed configuration)
+    devs = run_families(api, fams, api.FS_COLBLOCK64, want_rows=False, want_leaves=False)
+    for f, d in zip(fams, devs):
+        check_family(oracle, f, d)
