@@ -6,8 +6,10 @@
 // share a key, NaN gets the lowest key).  One workgroup serves one request:
 //   1. radix select (4 passes of 8 bits, histogram in LDS) finds the key of the k-th
 //      best entry and how many entries that tie with it still fit;
-//   2. an index-ordered sweep collects every entry above that key plus the lowest-index
-//      ties, as 64-bit composites (key, ~index) in LDS;
+//   2. every wavefront owns a contiguous slice of the scores; it counts the entries above
+//      that key and the ties in its slice, the counts are scanned, and a second sweep places
+//      every entry above the key plus the lowest-index ties as 64-bit composites
+//      (key, ~index) in LDS;
 //   3. a bitonic sort of the composites gives the final order; all composites differ, so
 //      the result is unique.
 #include "fs_internal.h"
@@ -25,26 +27,21 @@ __device__ __forceinline__ uint32_t score_key(float s)
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-// Exclusive prefix count of `flag` over the block in thread order; `total` gets the sum.
-// `wave_cnt` is LDS scratch of 16 ints.  Contains block barriers.
-__device__ __forceinline__ int block_prefix_count(bool flag, int *wave_cnt, int &total)
+constexpr int kTopkWaves = kTopkThreads / 64;
+constexpr int kTopkUnroll = 8;     // loads in flight per thread
+
+// Keys of kTopkUnroll consecutive 64-element pieces starting at `base`, this lane's element of
+// each; pieces past `end` read a clamped address and are flagged invalid by the caller.
+__device__ __forceinline__ void load_keys(const float *__restrict__ score, int base, int end,
+                                          int lane, uint32_t (&key)[kTopkUnroll])
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const unsigned long long b = __ballot(flag);
-    const int before = __popcll(b & ((1ull << lane) - 1ull));
-    __syncthreads();
-    if (lane == 0)
-        wave_cnt[wave] = __popcll(b);
-    __syncthreads();
-    int base = 0, sum = 0;
-    for (int w = 0; w < kTopkThreads / 64; ++w) {
-        const int c = wave_cnt[w];
-        if (w < wave)
-            base += c;
-        sum += c;
-    }
-    total = sum;
-    return base + before;
+    float v[kTopkUnroll];
+#pragma unroll
+    for (int u = 0; u < kTopkUnroll; ++u)
+        v[u] = score[min(base + u * 64 + lane, end - 1)];
+#pragma unroll
+    for (int u = 0; u < kTopkUnroll; ++u)
+        key[u] = score_key(v[u]);
 }
 
 __global__ void __launch_bounds__(kTopkThreads)
@@ -54,7 +51,7 @@ topk_kernel(const TopkDesc *__restrict__ descs)
     const TopkDesc d = descs[blockIdx.x];
     const int n = d.n, k = d.k;
     const int kk = min(n, k);
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *__restrict__ score = d.score;
 
     for (int j = kk + tid; j < k; j += kTopkThreads) {
@@ -68,8 +65,13 @@ topk_kernel(const TopkDesc *__restrict__ descs)
     while (kpow2 < kk)
         kpow2 <<= 1;
     int *hist = (int *)(cand + kpow2);    // 256 ints
-    int *wave_cnt = hist + 256;           // 16 ints
-    int *sel = wave_cnt + 16;             // [0] digit, [1] remaining need
+    int *wave_cnt = hist + 256;           // 2 x 16 ints: per-wavefront counts (above, equal)
+    int *sel = wave_cnt + 2 * kTopkWaves; // [0] digit, [1] remaining need
+
+    // Every wavefront owns a contiguous, 64-aligned slice of the scores: slices in wavefront
+    // order are the scores in index order.
+    const int per_wave = (((n + kTopkWaves - 1) / kTopkWaves) + 63) & ~63;
+    const int w_begin = min(wave * per_wave, n), w_end = min(w_begin + per_wave, n);
 
     // ---- 1. key of the kk-th best entry ----
     uint32_t prefix = 0, mask = 0;
@@ -80,17 +82,22 @@ topk_kernel(const TopkDesc *__restrict__ descs)
                 hist[tid] = 0;
             __syncthreads();
             int run_digit = -1, run = 0;
-            for (int i = tid; i < n; i += kTopkThreads) {
-                const uint32_t key = score_key(score[i]);
-                if ((key & mask) == prefix) {
-                    const int dg = (key >> shift) & 255;
-                    if (dg != run_digit) {
-                        if (run)
-                            atomicAdd(&hist[run_digit], run);
-                        run_digit = dg;
-                        run = 0;
+            for (int base = w_begin; base < w_end; base += 64 * kTopkUnroll) {
+                uint32_t key[kTopkUnroll];
+                load_keys(score, base, w_end, lane, key);
+#pragma unroll
+                for (int u = 0; u < kTopkUnroll; ++u) {
+                    const bool valid = base + u * 64 + lane < w_end;
+                    if (valid && (key[u] & mask) == prefix) {
+                        const int dg = (key[u] >> shift) & 255;
+                        if (dg != run_digit) {
+                            if (run)
+                                atomicAdd(&hist[run_digit], run);
+                            run_digit = dg;
+                            run = 0;
+                        }
+                        ++run;
                     }
-                    ++run;
                 }
             }
             if (run)
@@ -118,28 +125,50 @@ topk_kernel(const TopkDesc *__restrict__ descs)
     const uint32_t tau = prefix;
     const int need_eq = need;
 
-    // ---- 2. collect, in index order ----
-    int gt_done = 0, eq_done = 0;
-    for (int base = 0; base < n; base += kTopkThreads) {
-        const int i = base + tid;
-        uint32_t key = 0;
-        bool gt = false, eq = false;
-        if (i < n) {
-            key = score_key(score[i]);
-            gt = key > tau;
-            eq = key == tau;
+    // ---- 2. collect, in index order: count per wavefront, scan, then place ----
+    int my_gt = 0, my_eq = 0;
+    for (int base = w_begin; base < w_end; base += 64 * kTopkUnroll) {
+        uint32_t key[kTopkUnroll];
+        load_keys(score, base, w_end, lane, key);
+#pragma unroll
+        for (int u = 0; u < kTopkUnroll; ++u) {
+            const bool valid = base + u * 64 + lane < w_end;
+            my_gt += __popcll(__ballot(valid && key[u] > tau));
+            my_eq += __popcll(__ballot(valid && key[u] == tau));
         }
-        int tot_gt, tot_eq;
-        const int r_gt = block_prefix_count(gt, wave_cnt, tot_gt);
-        const int r_eq = block_prefix_count(eq, wave_cnt, tot_eq);
-        const unsigned long long comp =
-            ((unsigned long long)key << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)i);
-        if (gt)
-            cand[gt_done + r_gt] = comp;                    // fewer than kk of these exist
-        else if (eq && eq_done + r_eq < need_eq)
-            cand[kk - 1 - (eq_done + r_eq)] = comp;
-        gt_done += tot_gt;
-        eq_done += tot_eq;
+    }
+    if (lane == 0) {
+        wave_cnt[wave] = my_gt;
+        wave_cnt[kTopkWaves + wave] = my_eq;
+    }
+    __syncthreads();
+    int gt_before = 0, eq_before = 0;
+    for (int w = 0; w < wave; ++w) {
+        gt_before += wave_cnt[w];
+        eq_before += wave_cnt[kTopkWaves + w];
+    }
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int base = w_begin; base < w_end; base += 64 * kTopkUnroll) {
+        uint32_t key[kTopkUnroll];
+        load_keys(score, base, w_end, lane, key);
+#pragma unroll
+        for (int u = 0; u < kTopkUnroll; ++u) {
+            const int i = base + u * 64 + lane;
+            const bool valid = i < w_end;
+            const bool gt = valid && key[u] > tau, eq = valid && key[u] == tau;
+            const unsigned long long bg = __ballot(gt), be = __ballot(eq);
+            const unsigned long long comp =
+                ((unsigned long long)key[u] << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)i);
+            if (gt) {
+                cand[gt_before + __popcll(bg & below)] = comp;       // fewer than kk of these exist
+            } else if (eq) {
+                const int rank = eq_before + __popcll(be & below);   // index order among the ties
+                if (rank < need_eq)
+                    cand[kk - 1 - rank] = comp;
+            }
+            gt_before += __popcll(bg);
+            eq_before += __popcll(be);
+        }
     }
     for (int j = kk + tid; j < kpow2; j += kTopkThreads)
         cand[j] = 0ull;                                     // below every real composite
@@ -174,7 +203,7 @@ int launch_topk(const TopkDesc *d_desc, int n_requests, int max_k, hipStream_t s
     int kpow2 = 1;
     while (kpow2 < max_k)
         kpow2 <<= 1;
-    const size_t lds = (size_t)kpow2 * 8 + (256 + 16 + 2) * sizeof(int);
+    const size_t lds = (size_t)kpow2 * 8 + (256 + 2 * (kTopkThreads / 64) + 2) * sizeof(int);
     static size_t configured[16] = {0};
     int dev = 0;
     FS_HIP(hipGetDevice(&dev));
