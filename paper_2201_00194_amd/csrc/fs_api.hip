@@ -327,8 +327,8 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
             d.bin_feats_per_group = per_group;                      // >= 1 by model packing
             d.bin_groups = (a.model->n_features + per_group - 1) / per_group;
             // enough workgroups to fill the chip even for a small family
-            int64_t tpb = tiles * d.bin_groups / 2048;
-            if (tpb < 2) tpb = 2;
+            int64_t tpb = tiles * d.bin_groups / 512;
+            if (tpb < 8) tpb = 8;
             if (tpb > kBinTilesPerBlock) tpb = kBinTilesPerBlock;
             d.bin_tiles_per_block = (int32_t)tpb;
             bin_blocks += (int64_t)d.bin_groups * ((tiles + tpb - 1) / tpb);

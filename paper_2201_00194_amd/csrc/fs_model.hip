@@ -510,8 +510,8 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                 perfect = tree_is_perfect(split_feature + o, left + o, right + o, tree_off[t + 1] - o,
                                           &depth);
             }
-            // worth it when the fp32 format gets fewer than ~10 trees into a chunk
-            if (perfect && (want == 1 || depth >= 9) && depth <= 12)
+            // measured: pays from depth 8 on (3 KB per tree in the 8-byte-node format)
+            if (perfect && (want == 1 || depth >= 8) && depth <= 12)
                 build_rank_format(m, n_features, n_trees, depth, tree_off, split_feature, threshold,
                                   left, right, value, &rk_nodes, &rk_ids, &cuts);
         }

@@ -175,29 +175,39 @@ int launch_rank_code(const FamDesc *d_desc, int n_families, int total_blocks, hi
 // A split word is rank(thr) << 16 | feature*128.
 
 // K trees at once for this lane's row.  base[k] = LDS address of tree k; the 1-based heap
-// index i addresses base + 4*i.
+// index i lives at A = base + 4*i, and the step i' = 2i + c is taken on the address itself:
+// A' = 2A + (4c - base)   (one select between two per-tree constants and one shift-add).
 template <int K>
 __device__ __forceinline__ void rank_walk(const uint32_t (&base)[K], int depth, uint32_t lane_base,
                                           uint32_t (&idx)[K], float (&v)[K])
 {
+    uint32_t A[K], left[K], right[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k)
-        idx[k] = 1u;
+    for (int k = 0; k < K; ++k) {
+        A[k] = base[k] + 4u;
+        left[k] = 0u - base[k];
+        right[k] = 4u - base[k];
+        // keep the two constants as they are: the compiler would otherwise fold the select
+        // into select(0,4) - base and spend two more instructions per visit
+        asm volatile("" : "+v"(left[k]), "+v"(right[k]));
+    }
     for (int l = 0; l < depth; ++l) {
         uint32_t nd[K], x[K];
 #pragma unroll
         for (int k = 0; k < K; ++k)
-            nd[k] = lds_u(base[k] + 4u * idx[k]);
+            nd[k] = lds_u(A[k]);
 #pragma unroll
         for (int k = 0; k < K; ++k)
             x[k] = lds_u16((nd[k] & 0xFFFFu) + lane_base);
 #pragma unroll
         for (int k = 0; k < K; ++k)
-            idx[k] = 2u * idx[k] + ((x[k] < (nd[k] >> 16)) ? 0u : 1u);
+            A[k] = (A[k] << 1) + ((x[k] < (nd[k] >> 16)) ? left[k] : right[k]);
     }
 #pragma unroll
-    for (int k = 0; k < K; ++k)
-        v[k] = lds_f(base[k] + 4u * idx[k]);
+    for (int k = 0; k < K; ++k) {
+        v[k] = lds_f(A[k]);
+        idx[k] = (A[k] - base[k]) >> 2;
+    }
 }
 
 template <int K, bool DUMP>
