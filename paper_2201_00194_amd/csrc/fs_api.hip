@@ -248,8 +248,10 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
                         (long long)a.n_rows);
         if (!a.row_score)
             scratch_floats += (size_t)a.n_rows;
-        if (a.model->rank_ok && a.layout == FS_COLBLOCK64)   // u16 rank tiles, in float units
+        if (a.model->rank_ok)                                // u16 rank tiles, in float units
             scratch_floats += (size_t)((a.n_rows + 63) / 64) * 32 * (size_t)a.model->n_features + 4;
+        if ((a.model->rank_ok || a.model->lds_ok) && a.layout == FS_ROWMAJOR)   // re-tiled copy
+            scratch_floats += (size_t)((a.n_rows + 63) / 64) * 64 * (size_t)a.model->n_features + 4;
     }
     rc = ensure_scratch(ctx, scratch_floats);
     if (rc != FS_OK)
@@ -261,7 +263,7 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         return rc;
     FamDesc *h = (FamDesc *)slot->h_buf;
     int64_t trav_blocks = 0, seg_blocks = 0, lds_blocks[kLdsModes] = {0, 0};
-    int64_t rk_blocks = 0, bin_blocks = 0;
+    int64_t rk_blocks = 0, bin_blocks = 0, retile_blocks = 0;
     bool rk_dump = false;
     bool dump[kLdsModes] = {false, false};
     size_t scratch_pos = 0;
@@ -297,6 +299,23 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         d.lds_tile0 = a.model->lds_tile0;
         d.lds_tiles = a.model->lds_tiles;
         d.compact = a.model->compact ? 1 : 0;
+        // Row-major features of a model that has an LDS format are re-tiled into scratch first
+        // (one extra pass over the features); from then on the family is column-blocked.
+        d.rowmajor_src = nullptr;
+        d.retile_block0 = (int32_t)retile_blocks;
+        d.retile_colblocks = 0;
+        const bool fast = a.model->rank_ok || a.model->lds_ok;
+        if (fast && a.layout == FS_ROWMAJOR && a.n_rows > 0) {
+            const int64_t tiles = (a.n_rows + 63) / 64;
+            scratch_pos = (scratch_pos + 3) & ~(size_t)3;
+            d.rowmajor_src = a.features;
+            d.features = ctx->scratch + scratch_pos;
+            d.layout = FS_COLBLOCK64;
+            scratch_pos += (size_t)tiles * 64 * (size_t)a.model->n_features;
+            d.retile_colblocks = (a.model->n_features + 127) / 128;
+            retile_blocks += tiles * d.retile_colblocks;
+        }
+        const bool colblock = d.layout == FS_COLBLOCK64;
         d.rk_nodes = a.model->d_rk_nodes;
         d.rk_ids = a.model->d_rk_ids;
         d.cuts = a.model->d_cuts;
@@ -316,7 +335,7 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         // Column-blocked features: deep perfect-tree models are rank-coded first and walked by
         // the rank kernel, other models that fit the LDS format take the LDS kernel; everything
         // else is walked from global memory.
-        if (a.model->rank_ok && a.layout == FS_COLBLOCK64) {
+        if (a.model->rank_ok && colblock) {
             const int64_t tiles = (a.n_rows + 63) / 64;
             scratch_pos = (scratch_pos + 3) & ~(size_t)3;            // 16-byte aligned tiles
             d.ranks = (uint16_t *)(ctx->scratch + scratch_pos);
@@ -335,7 +354,7 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
             rk_blocks += (tiles + a.model->rk_tiles - 1) / a.model->rk_tiles;
             if (a.leaf_idx && a.n_rows > 0)
                 rk_dump = true;
-        } else if (a.model->lds_ok && a.layout == FS_COLBLOCK64) {
+        } else if (a.model->lds_ok && colblock) {
             const int64_t tiles = (a.n_rows + 63) / 64;
             const int md = a.model->lds_mode;
             lds_blocks[md] += (tiles + a.model->lds_tiles - 1) / a.model->lds_tiles;
@@ -348,7 +367,8 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
     }
     if (trav_blocks >= ((int64_t)1 << 31) || seg_blocks >= ((int64_t)1 << 31) ||
         lds_blocks[0] >= ((int64_t)1 << 31) || lds_blocks[1] >= ((int64_t)1 << 31) ||
-        rk_blocks >= ((int64_t)1 << 31) || bin_blocks >= ((int64_t)1 << 31))
+        rk_blocks >= ((int64_t)1 << 31) || bin_blocks >= ((int64_t)1 << 31) ||
+        retile_blocks >= ((int64_t)1 << 31))
         return fail(FS_EUNSUPPORTED, "fs_score_families: too much work for one submission");
 
     FS_HIP(hipMemcpyAsync(slot->d_buf, slot->h_buf, sizeof(FamDesc) * (size_t)n_families,
@@ -356,6 +376,11 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
     slot->used = true;
     const FamDesc *d_desc = (const FamDesc *)slot->d_buf;
     rc = FS_OK;
+    if (retile_blocks > 0) {
+        prof_start(kKernPack, stream);
+        rc = launch_retile(d_desc, n_families, (int)retile_blocks, stream);
+        prof_stop(stream);
+    }
     for (int md = 0; md < kLdsModes && rc == FS_OK; ++md) {
         if (lds_blocks[md] == 0)
             continue;

@@ -146,6 +146,10 @@ struct FamDesc {
     int32_t bin_groups;              // feature groups of this family in the rank-coding grid
     int32_t bin_feats_per_group;
     int32_t bin_tiles_per_block;
+    // row-major input: re-tiled into scratch before the LDS kernels (features then points there)
+    const float *rowmajor_src;
+    int32_t retile_block0;           // first block of the re-tiling grid
+    int32_t retile_colblocks;        // column blocks per tile (0: family not re-tiled)
     int32_t cut_bits;                // threshold tables are padded to 2^cut_bits entries
     int32_t pad;
 };
@@ -168,6 +172,7 @@ int launch_traverse_rank(const FamDesc *d_desc, int n_families, int total_blocks
                          hipStream_t stream);
 int launch_segsum(const FamDesc *d_desc, int n_families, int total_blocks, hipStream_t stream);
 int launch_topk(const TopkDesc *d_desc, int n_requests, int max_k, hipStream_t stream);
+int launch_retile(const FamDesc *d_desc, int n_families, int total_blocks, hipStream_t stream);
 int launch_pack_colblock64(const float *in, int64_t n_rows, int32_t n_features, float *out,
                            hipStream_t stream);
 

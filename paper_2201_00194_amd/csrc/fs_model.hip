@@ -441,12 +441,22 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                 m->compact = compact;
                 m->lds_tiles = best_t;
                 m->lds_mode = best_mode;
+                // Even chunks: a greedy fill would leave a short last chunk whose few trees cannot
+                // keep the wavefronts busy.  Estimate the chunk count from the average tree and
+                // cap every chunk at ceil(n_trees / chunks).
+                size_t est_per = best_avail / (avg_tree + 4 + per_tree_val);
+                const size_t est_img = (chunk_image_limit(best_mode) - 16) / (avg_tree + 4);
+                if (est_per > est_img) est_per = est_img;
+                if (est_per > (size_t)kMaxChunkTrees) est_per = kMaxChunkTrees;
+                if (est_per < 1) est_per = 1;
+                const int est_chunks = (int)(((size_t)n_trees + est_per - 1) / est_per);
+                const int even_cap = (n_trees + est_chunks - 1) / est_chunks;
                 int t = 0;
                 while (t < n_trees) {
                     // how many trees fit: chunk image (table included) + their value rows
                     int cnt = 0;
                     size_t body = 0;
-                    while (t + cnt < n_trees && cnt < kMaxChunkTrees) {
+                    while (t + cnt < n_trees && cnt < kMaxChunkTrees && cnt < even_cap) {
                         const size_t b = trees[(size_t)(t + cnt)].words.size() * 4;
                         const size_t table = ((size_t)(cnt + 1) * 4 + 7) & ~(size_t)7;
                         const size_t img = (table + body + b + 15) & ~(size_t)15;

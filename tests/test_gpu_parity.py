@@ -278,3 +278,67 @@ def test_rank_coded_path_special_values_and_shallow_trees(api, oracle, monkeypat
     devs = run_families(api, fams, api.FS_COLBLOCK64, want_rows=False, want_leaves=False)
     for f, d in zip(fams, devs):
         check_family(oracle, f, d)
+
+
+def test_models_outside_the_lds_formats_take_the_global_kernel(api, oracle):
+    """More than 255 features, or trees too large for an LDS chunk: walked from global memory,
+    in either layout."""
+    wide = W.make_small_family(seed=401, n_programs=150, stmts=(1, 6), n_trees=12, depth=5,
+                               early_leaf_q=0.2, n_features=300, k=20)
+    deep = W.make_small_family(seed=402, n_programs=90, stmts=(2, 3), n_trees=3, depth=13, k=10)
+    for layout in LAYOUTS:
+        devs = run_families(api, [wide, deep], layout)
+        for f, d in zip([wide, deep], devs):
+            check_family(oracle, f, d)
+    api.fs_profile_begin(16)
+    run_families(api, [wide, deep], api.FS_COLBLOCK64)
+    prof = api.fs_profile_end()
+    assert prof["traverse_global"][1] >= 1 and prof["traverse"][1] == 0
+
+
+def test_rowmajor_input_is_retiled_into_the_fast_kernels(api, oracle):
+    case = W.make_case(1, seed=5, scale=0.02, trees=30)       # perfect depth-8 trees: rank path
+    irregular = W.make_case(4, seed=5, scale=0.02, trees=20)  # 8-byte-node LDS path
+    fams = case.families[:3] + irregular.families[:3]
+    api.fs_profile_begin(32)
+    devs = run_families(api, fams, api.FS_ROWMAJOR)
+    prof = api.fs_profile_end()
+    for f, d in zip(fams, devs):
+        check_family(oracle, f, d)
+    assert prof["pack"][1] == 1 and prof["traverse_global"][1] == 0
+    assert prof["traverse"][1] == 1 and prof["traverse_rank"][1] == 1
+
+
+def test_foresee_step_shape_many_small_pools_sharing_a_family_model(api, oracle):
+    """The family-scoped step of the paper's Algorithm 1: the family's one model estimates the
+    candidates of several member subgraphs, and g*p = 16 candidates per subgraph go on
+    (Section 4.2; p = 0.25, g = 64).  Here: 5 families, 3-6 subgraph pools each, pools of
+    320..4288 programs (the paper's Section 3.2 example sizes), one batched call for all."""
+    import torch
+    rng = np.random.default_rng(77)
+    host, devs = [], []
+    models = {}
+    for fam in range(5):
+        base = W.make_small_family(seed=500 + fam, n_programs=8, stmts=(1, 8), n_trees=30,
+                                   depth=7, early_leaf_q=0.0 if fam % 2 else 0.25, k=16)
+        for sub in range(int(rng.integers(3, 7))):
+            n_prog = int(rng.choice([320, 1024, 2048, 2304, 4288]))
+            pool = W.make_small_family(seed=1000 * fam + sub, n_programs=n_prog, stmts=(1, 8),
+                                       n_trees=1, depth=1, k=16)
+            pool.model = base.model                      # the family's model, shared
+            host.append(pool)
+    shared = {}
+    for f in host:
+        key = id(f.model)
+        if key not in shared:
+            shared[key] = api.fs_model.from_arrays(f.model)
+        tmp = api.DeviceFamily(f, want_row_score=True, want_leaf_idx=True)
+        tmp.model.destroy()
+        tmp.model = shared[key]                          # one fs_model per family
+        devs.append(tmp)
+    api.fs_score_families([d.family() for d in devs])
+    api.fs_topk([d.topk_request() for d in devs])
+    torch.cuda.synchronize()
+    for f, d in zip(host, devs):
+        check_family(oracle, f, d)
+    assert len(shared) == 5 and len(devs) >= 15
