@@ -449,23 +449,85 @@ extern "C" int fs_topk(int32_t n_requests, const fs_topk_req *reqs, void *stream
     int rc = current_ctx(&ctx);
     if (rc != FS_OK)
         return rc;
+    // Long requests are cut into slices (one workgroup each) whose candidates a second
+    // kernel merges; the others take one workgroup and finish in the first kernel.
+    auto slices_of = [](const fs_topk_req &r) {
+        if (r.n < kTopkSliceMin || r.k == 0)
+            return 1;
+        int kp = 1;
+        while (kp < r.k)
+            kp <<= 1;
+        int s = kTopkMergeCap / kp;
+        if (s > kTopkMaxSlices)
+            s = kTopkMaxSlices;
+        return s >= 2 ? s : 1;
+    };
+    size_t n_blocks = 0, n_merge = 0, comp_total = 0;
+    int max_comp = 0;
+    for (int i = 0; i < n_requests; ++i) {
+        const int s = slices_of(reqs[i]);
+        n_blocks += (size_t)s;
+        if (s > 1) {
+            ++n_merge;
+            comp_total += (size_t)s * (size_t)reqs[i].k;
+            int kp = 1;
+            while (kp < reqs[i].k)
+                kp <<= 1;
+            if (s * kp > max_comp)
+                max_comp = s * kp;
+        }
+    }
+    if (comp_total) {
+        rc = ensure_scratch(ctx, comp_total * 2);
+        if (rc != FS_OK)
+            return rc;
+    }
+    const size_t desc_bytes = sizeof(TopkDesc) * n_blocks;
+    const size_t merge_off = (desc_bytes + 15) & ~(size_t)15;
+    const size_t total_bytes = merge_off + sizeof(TopkMergeDesc) * n_merge;
     Slot *slot = nullptr;
-    rc = acquire_slot(ctx, sizeof(TopkDesc) * (size_t)n_requests, &slot);
+    rc = acquire_slot(ctx, total_bytes, &slot);
     if (rc != FS_OK)
         return rc;
     TopkDesc *h = (TopkDesc *)slot->h_buf;
+    TopkMergeDesc *hm = (TopkMergeDesc *)((char *)slot->h_buf + merge_off);
+    unsigned long long *comp = (unsigned long long *)ctx->scratch;
+    size_t b = 0, m = 0;
     for (int i = 0; i < n_requests; ++i) {
-        h[i].score = reqs[i].score;
-        h[i].out_idx = reqs[i].out_idx;
-        h[i].out_score = reqs[i].out_score;
-        h[i].n = reqs[i].n;
-        h[i].k = reqs[i].k;
+        const fs_topk_req &r = reqs[i];
+        const int s = slices_of(r);
+        const int per = s > 1 ? (((r.n + s - 1) / s) + 63) & ~63 : r.n;
+        for (int j = 0; j < s; ++j, ++b) {
+            h[b].score = r.score;
+            h[b].out_idx = r.out_idx;
+            h[b].out_score = r.out_score;
+            h[b].n = r.n;
+            h[b].k = r.k;
+            const long long lo = (long long)j * per, hi = lo + per;
+            h[b].sub_begin = (int32_t)(lo < r.n ? lo : r.n);
+            h[b].sub_end = (int32_t)(hi < r.n ? hi : r.n);
+            h[b].comp_out = s > 1 ? comp + (size_t)j * (size_t)r.k : nullptr;
+        }
+        if (s > 1) {
+            hm[m].comp_in = comp;
+            hm[m].score = r.score;
+            hm[m].out_idx = r.out_idx;
+            hm[m].out_score = r.out_score;
+            hm[m].n_comp = s * r.k;
+            hm[m].n = r.n;
+            hm[m].k = r.k;
+            hm[m].pad = 0;
+            comp += (size_t)s * (size_t)r.k;
+            ++m;
+        }
     }
-    FS_HIP(hipMemcpyAsync(slot->d_buf, slot->h_buf, sizeof(TopkDesc) * (size_t)n_requests,
-                          hipMemcpyHostToDevice, stream));
+    FS_HIP(hipMemcpyAsync(slot->d_buf, slot->h_buf, total_bytes, hipMemcpyHostToDevice, stream));
     slot->used = true;
     prof_start(kKernTopk, stream);
-    rc = launch_topk((const TopkDesc *)slot->d_buf, n_requests, max_k, stream);
+    rc = launch_topk((const TopkDesc *)slot->d_buf, (int)n_blocks, max_k, stream);
+    if (rc == FS_OK && n_merge)
+        rc = launch_topk_merge((const TopkMergeDesc *)((const char *)slot->d_buf + merge_off),
+                               (int)n_merge, max_comp, stream);
     prof_stop(stream);
     hipError_t e = hipEventRecord(slot->done, stream);
     if (rc != FS_OK)

@@ -154,13 +154,30 @@ struct FamDesc {
     int32_t pad;
 };
 
+// One workgroup of the first top-k stage: the whole request, or one slice of a large one.
 struct TopkDesc {
     const float *score;
     int32_t *out_idx;
     float *out_score;      // may be NULL
-    int32_t n;
+    int32_t n;             // entries of the request
     int32_t k;
+    int32_t sub_begin, sub_end;      // the slice [sub_begin, sub_end) this workgroup ranks
+    unsigned long long *comp_out;    // NULL: final answer to out_idx/out_score; else the slice's
+                                     // best k (key, ~index) composites, best first, 0-padded
 };
+
+// Second stage of a large request: merge the slices' candidates.
+struct TopkMergeDesc {
+    const unsigned long long *comp_in;   // n_comp composites (0 = padding)
+    const float *score;
+    int32_t *out_idx;
+    float *out_score;      // may be NULL
+    int32_t n_comp;
+    int32_t n;             // entries of the request
+    int32_t k;
+    int32_t pad;
+};
+
 
 // ---- launchers (each returns FS_OK or records an error) ---------------------------------------
 int launch_traverse_global(const FamDesc *d_desc, int n_families, int total_blocks,
@@ -171,7 +188,12 @@ int launch_rank_code(const FamDesc *d_desc, int n_families, int total_blocks, hi
 int launch_traverse_rank(const FamDesc *d_desc, int n_families, int total_blocks, bool dump,
                          hipStream_t stream);
 int launch_segsum(const FamDesc *d_desc, int n_families, int total_blocks, hipStream_t stream);
-int launch_topk(const TopkDesc *d_desc, int n_requests, int max_k, hipStream_t stream);
+int launch_topk(const TopkDesc *d_desc, int n_blocks, int max_k, hipStream_t stream);
+// max_padded: largest (slices * k rounded up to a power of two) over the requests
+int launch_topk_merge(const TopkMergeDesc *d_desc, int n_requests, int max_padded, hipStream_t stream);
+constexpr int kTopkSliceMin = 32768;     // requests at least this long are split into slices
+constexpr int kTopkMaxSlices = 16;
+constexpr int kTopkMergeCap = 16384;     // composites (lists padded to a power of two) the merge holds in LDS
 int launch_retile(const FamDesc *d_desc, int n_families, int total_blocks, hipStream_t stream);
 int launch_pack_colblock64(const float *in, int64_t n_rows, int32_t n_features, float *out,
                            hipStream_t stream);

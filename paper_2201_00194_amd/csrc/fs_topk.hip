@@ -12,6 +12,11 @@
 //      (key, ~index) in LDS;
 //   3. a bitonic sort of the composites gives the final order; all composites differ, so
 //      the result is unique.
+// A long request (>= 32768 entries) is cut into up to 16 slices, one workgroup each, which
+// leave their best k composites in scratch, best first; a second kernel merges the slices'
+// lists pairwise in LDS, keeping the best k of every pair, and writes the answer.  The union of the slices' best k holds the
+// request's best k, and composites order the same way everywhere, so nothing changes in the
+// result.
 #include "fs_internal.h"
 
 namespace fs {
@@ -49,15 +54,21 @@ topk_kernel(const TopkDesc *__restrict__ descs)
 {
     extern __shared__ unsigned long long cand[];   // [kpow2] then small scratch
     const TopkDesc d = descs[blockIdx.x];
-    const int n = d.n, k = d.k;
+    const int n = d.sub_end - d.sub_begin, k = d.k;   // this workgroup's entries
     const int kk = min(n, k);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const float *__restrict__ score = d.score;
+    const float *__restrict__ score = d.score + d.sub_begin;
+    const uint32_t idx0 = (uint32_t)d.sub_begin;
 
-    for (int j = kk + tid; j < k; j += kTopkThreads) {
-        d.out_idx[j] = -1;
-        if (d.out_score)
-            d.out_score[j] = -__builtin_inff();
+    if (d.comp_out) {
+        for (int j = kk + tid; j < k; j += kTopkThreads)
+            d.comp_out[j] = 0ull;
+    } else {
+        for (int j = kk + tid; j < k; j += kTopkThreads) {
+            d.out_idx[j] = -1;
+            if (d.out_score)
+                d.out_score[j] = -__builtin_inff();
+        }
     }
     if (kk == 0)
         return;
@@ -158,7 +169,8 @@ topk_kernel(const TopkDesc *__restrict__ descs)
             const bool gt = valid && key[u] > tau, eq = valid && key[u] == tau;
             const unsigned long long bg = __ballot(gt), be = __ballot(eq);
             const unsigned long long comp =
-                ((unsigned long long)key[u] << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)i);
+                ((unsigned long long)key[u] << 32) |
+                (unsigned long long)(0xFFFFFFFFu - (idx0 + (uint32_t)i));
             if (gt) {
                 cand[gt_before + __popcll(bg & below)] = comp;       // fewer than kk of these exist
             } else if (eq) {
@@ -190,12 +202,100 @@ topk_kernel(const TopkDesc *__restrict__ descs)
             __syncthreads();
         }
     }
+    if (d.comp_out) {
+        for (int j = tid; j < kk; j += kTopkThreads)
+            d.comp_out[j] = cand[j];
+        return;
+    }
     for (int j = tid; j < kk; j += kTopkThreads) {
         const uint32_t idx = 0xFFFFFFFFu - (uint32_t)(cand[j] & 0xFFFFFFFFull);
         d.out_idx[j] = (int32_t)idx;
         if (d.out_score)
-            d.out_score[j] = score[idx];
+            d.out_score[j] = d.score[idx];
     }
+}
+
+// Second stage: the slices' sorted candidate lists into LDS (each padded to kp = 2^q >= k
+// entries), then a tree of pairwise merges that each keep only the better kp entries:
+// max(A[i], B[kp-1-i]) holds the best kp of two descending lists as a bitonic sequence, and
+// q compare-exchange rounds sort it.  What is left in list 0 is the answer.
+__global__ void __launch_bounds__(kTopkThreads)
+topk_merge_kernel(const TopkMergeDesc *__restrict__ descs)
+{
+    extern __shared__ unsigned long long cand[];
+    const TopkMergeDesc d = descs[blockIdx.x];
+    const int tid = threadIdx.x;
+    const int k = d.k, lists = d.n_comp / k;
+    int q = 0;
+    while ((1 << q) < k)
+        ++q;
+    const int kp = 1 << q;
+    for (int j = tid; j < lists * kp; j += kTopkThreads) {
+        const int l = j >> q, i = j & (kp - 1);
+        cand[j] = i < k ? d.comp_in[l * k + i] : 0ull;
+    }
+    __syncthreads();
+    for (int step = 1; step < lists; step <<= 1) {
+        const int groups = (lists + 2 * step - 1) / (2 * step);
+        for (int t = tid; t < groups * kp; t += kTopkThreads) {
+            const int a = (t >> q) * 2 * step, i = t & (kp - 1);
+            if (a + step < lists) {
+                const unsigned long long x = cand[a * kp + i], y = cand[(a + step) * kp + kp - 1 - i];
+                if (x < y)
+                    cand[a * kp + i] = y;
+            }
+        }
+        __syncthreads();
+        for (int stride = kp >> 1; stride > 0; stride >>= 1) {
+            for (int t = tid; t < groups * (kp >> 1); t += kTopkThreads) {
+                const int a = (t >> (q - 1)) * 2 * step, u = t & ((kp >> 1) - 1);
+                if (a + step < lists) {
+                    const int lo = a * kp + (((u & ~(stride - 1)) << 1) | (u & (stride - 1)));
+                    const int hi = lo + stride;
+                    const unsigned long long x = cand[lo], y = cand[hi];
+                    if (x < y) {
+                        cand[lo] = y;
+                        cand[hi] = x;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    const int kk = min(d.n, k);
+    for (int j = tid; j < k; j += kTopkThreads) {
+        if (j < kk) {
+            const uint32_t idx = 0xFFFFFFFFu - (uint32_t)(cand[j] & 0xFFFFFFFFull);
+            d.out_idx[j] = (int32_t)idx;
+            if (d.out_score)
+                d.out_score[j] = d.score[idx];
+        } else {
+            d.out_idx[j] = -1;
+            if (d.out_score)
+                d.out_score[j] = -__builtin_inff();
+        }
+    }
+}
+
+int launch_topk_merge(const TopkMergeDesc *d_desc, int n_requests, int max_padded, hipStream_t stream)
+{
+    if (max_padded > kTopkMergeCap)
+        return fail(FS_EUNSUPPORTED, "top-k merge of %d candidates exceeds %d", max_padded, kTopkMergeCap);
+    const size_t lds = (size_t)max_padded * 8;
+    static size_t configured[16] = {0};
+    int dev = 0;
+    FS_HIP(hipGetDevice(&dev));
+    if (lds > 65536 && (dev < 0 || dev >= 16 || configured[dev] < lds)) {
+        FS_HIP(hipFuncSetAttribute((const void *)topk_merge_kernel,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        if (dev >= 0 && dev < 16)
+            configured[dev] = lds;
+    }
+    hipLaunchKernelGGL(topk_merge_kernel, dim3(n_requests), dim3(kTopkThreads), lds, stream, d_desc);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail_hip(e, "topk_merge_kernel launch");
+    return FS_OK;
 }
 
 int launch_topk(const TopkDesc *d_desc, int n_requests, int max_k, hipStream_t stream)

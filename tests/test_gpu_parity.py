@@ -187,6 +187,44 @@ def test_topk_standalone_ties_signed_zero_nan(api, oracle):
     assert np.array_equal(oi.cpu().numpy(), oracle.topk(sc, k)[0])
 
 
+def test_topk_long_requests_are_sliced_and_merged(api, oracle):
+    """Requests of 32768 entries or more take several workgroups plus a merge; mixed in one
+    submission with short ones.  Ties, NaN and constant scores must still come out in the
+    oracle's order (Section 3.2: sort by estimate, keep the top k)."""
+    import torch
+    rng = np.random.default_rng(11)
+    cases = []
+    cases.append((rng.standard_normal(32768).astype(np.float32), 64))
+    cases.append((rng.standard_normal(40001).astype(np.float32), 5000))      # 3 ragged slices
+    cases.append((np.full(50000, -2.25, np.float32), 3000))                  # all tie: lowest indices
+    q = (rng.integers(-3, 3, 262144) / 2.0).astype(np.float32)
+    q[rng.integers(0, 262144, 1000)] = np.nan
+    q[rng.integers(0, 262144, 1000)] = -0.0
+    cases.append((q, 1024))
+    cases.append((rng.standard_normal(1000).astype(np.float32), 10))         # short, same launch
+    step = np.zeros(65536, np.float32)
+    step[60000:] = 1.0                                                       # best entries all in the last slice
+    cases.append((step, 8192))
+    cases.append((rng.standard_normal(33000).astype(np.float32), 16384))     # k too large to slice
+    cases.append((rng.standard_normal(100000).astype(np.float32), 1))
+    nanall = np.full(40000, np.nan, np.float32)
+    cases.append((nanall, 100))
+    reqs, outs = [], []
+    for sc, k in cases:
+        t = torch.from_numpy(sc).cuda()
+        oi = torch.full((k,), -7, dtype=torch.int32, device="cuda")
+        ov = torch.full((k,), float("nan"), dtype=torch.float32, device="cuda")
+        reqs.append(api.TopkRequest(t, sc.shape[0], k, oi, ov))
+        outs.append((oi, ov))
+    for _ in range(2):      # the second call reuses the candidate scratch
+        api.fs_topk(reqs)
+        torch.cuda.synchronize()
+        for (sc, k), (oi, ov) in zip(cases, outs):
+            idx, val = oracle.topk(sc, k)
+            assert np.array_equal(oi.cpu().numpy(), idx)
+            assert np.array_equal(ov.cpu().numpy().view(np.uint32), val.view(np.uint32))
+
+
 def test_repeat_calls_are_bit_identical_and_scratch_row_scores_work(api, oracle):
     import torch
     case = W.make_case(3, seed=4, scale=0.01, trees=25)
