@@ -460,6 +460,8 @@ extern "C" int fs_topk(int32_t n_requests, const fs_topk_req *reqs, void *stream
         int s = kTopkMergeCap / kp;
         if (s > kTopkMaxSlices)
             s = kTopkMaxSlices;
+        if (s > r.n / kTopkSliceEntries)
+            s = r.n / kTopkSliceEntries;
         return s >= 2 ? s : 1;
     };
     size_t n_blocks = 0, n_merge = 0, comp_total = 0;

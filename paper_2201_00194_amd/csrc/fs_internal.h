@@ -191,7 +191,8 @@ int launch_segsum(const FamDesc *d_desc, int n_families, int total_blocks, hipSt
 int launch_topk(const TopkDesc *d_desc, int n_blocks, int max_k, hipStream_t stream);
 // max_padded: largest (slices * k rounded up to a power of two) over the requests
 int launch_topk_merge(const TopkMergeDesc *d_desc, int n_requests, int max_padded, hipStream_t stream);
-constexpr int kTopkSliceMin = 32768;     // requests at least this long are split into slices
+constexpr int kTopkSliceMin = 8192;      // requests at least this long are split into slices
+constexpr int kTopkSliceEntries = 2048;  // of at least this many entries
 constexpr int kTopkMaxSlices = 16;
 constexpr int kTopkMergeCap = 16384;     // composites (lists padded to a power of two) the merge holds in LDS
 int launch_retile(const FamDesc *d_desc, int n_families, int total_blocks, hipStream_t stream);

@@ -12,7 +12,7 @@
 //      (key, ~index) in LDS;
 //   3. a bitonic sort of the composites gives the final order; all composites differ, so
 //      the result is unique.
-// A long request (>= 32768 entries) is cut into up to 16 slices, one workgroup each, which
+// A long request (>= 8192 entries) is cut into up to 16 slices, one workgroup each, which
 // leave their best k composites in scratch, best first; a second kernel merges the slices'
 // lists pairwise in LDS, keeping the best k of every pair, and writes the answer.  The union of the slices' best k holds the
 // request's best k, and composites order the same way everywhere, so nothing changes in the
@@ -72,7 +72,7 @@ topk_kernel(const TopkDesc *__restrict__ descs)
     }
     if (kk == 0)
         return;
-    int kpow2 = 1;
+    int kpow2 = 2;                        // at least 2: keeps the histogram 16-byte aligned
     while (kpow2 < kk)
         kpow2 <<= 1;
     int *hist = (int *)(cand + kpow2);    // 256 ints
@@ -114,15 +114,28 @@ topk_kernel(const TopkDesc *__restrict__ descs)
             if (run)
                 atomicAdd(&hist[run_digit], run);
             __syncthreads();
-            if (tid == 0) {
-                int above = 0, dg = 255;
-                for (; dg > 0; --dg) {
-                    if (above + hist[dg] >= need)
-                        break;
-                    above += hist[dg];
+            if (wave == 0) {
+                // The digit whose bin holds the need-th best entry: lane l owns bins 4l..4l+3,
+                // a suffix sum over the lanes gives the entries in higher bins.
+                const int4 c = *(const int4 *)&hist[4 * lane];
+                const int total = c.x + c.y + c.z + c.w;
+                int suffix = total;                       // inclusive: lanes >= this one
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) {
+                    const int v = __shfl_down(suffix, off);
+                    if (lane + off < 64)
+                        suffix += v;
                 }
-                sel[0] = dg;
-                sel[1] = need - above;
+                int above = suffix - total;
+                const int cnt[4] = {c.w, c.z, c.y, c.x};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (above < need && above + cnt[j] >= need) {
+                        sel[0] = 4 * lane + 3 - j;
+                        sel[1] = need - above;
+                    }
+                    above += cnt[j];
+                }
             }
             __syncthreads();
             prefix |= (uint32_t)sel[0] << shift;
@@ -300,7 +313,7 @@ int launch_topk_merge(const TopkMergeDesc *d_desc, int n_requests, int max_padde
 
 int launch_topk(const TopkDesc *d_desc, int n_requests, int max_k, hipStream_t stream)
 {
-    int kpow2 = 1;
+    int kpow2 = 2;
     while (kpow2 < max_k)
         kpow2 <<= 1;
     const size_t lds = (size_t)kpow2 * 8 + (256 + 2 * (kTopkThreads / 64) + 2) * sizeof(int);

@@ -188,7 +188,7 @@ def test_topk_standalone_ties_signed_zero_nan(api, oracle):
 
 
 def test_topk_long_requests_are_sliced_and_merged(api, oracle):
-    """Requests of 32768 entries or more take several workgroups plus a merge; mixed in one
+    """Requests of 8192 entries or more take several workgroups plus a merge; mixed in one
     submission with short ones.  Ties, NaN and constant scores must still come out in the
     oracle's order (Section 3.2: sort by estimate, keep the top k)."""
     import torch
@@ -202,6 +202,8 @@ def test_topk_long_requests_are_sliced_and_merged(api, oracle):
     q[rng.integers(0, 262144, 1000)] = -0.0
     cases.append((q, 1024))
     cases.append((rng.standard_normal(1000).astype(np.float32), 10))         # short, same launch
+    cases.append((rng.standard_normal(8192).astype(np.float32), 64))         # 4 slices
+    cases.append((rng.standard_normal(9000).astype(np.float32), 3000))       # 4 slices, k above a slice's length
     step = np.zeros(65536, np.float32)
     step[60000:] = 1.0                                                       # best entries all in the last slice
     cases.append((step, 8192))
