@@ -226,12 +226,13 @@ def main():
         # ---- CPU baseline: the oracle as it stands, on a bounded sample --------------------------
         threads = min(16, os.cpu_count() or 1)
         budget = 2.0e10                     # node visits: roughly 30 core-seconds of the oracle
-        share = budget / max(1.0, min(len(case.families), 4))
-        sample_rows, t_cpu, desc = 0, 0.0, []
+        remaining = budget
+        sample_rows, t_cpu, desc, whole = 0, 0.0, [], 0
         for fi, f in enumerate(case.families):
-            if len(desc) >= 4 or f.n_rows == 0:
+            if remaining <= 0 or f.n_rows == 0 or f.n_programs == 0:
                 continue
-            want_rows = int(share / max(1.0, f.model.n_trees * max(1.0, mean_path)))
+            per_row = f.model.n_trees * max(1.0, mean_path)
+            want_rows = int(remaining / max(1.0, per_row))
             p_end = int(np.searchsorted(f.prog_off, want_rows, side="right")) - 1
             p_end = max(1, min(f.n_programs, p_end))
             sub_off = f.prog_off[: p_end + 1]
@@ -243,11 +244,17 @@ def main():
             O.topk(ps, min(f.k, p_end))
             t_cpu += time.perf_counter() - c0
             sample_rows += rows
-            desc.append("family %d programs [0,%d) = %d rows" % (fi, p_end, rows))
+            remaining -= rows * per_row
+            if p_end == f.n_programs:
+                whole += 1
+            else:
+                desc.append("family %d programs [0,%d) = %d rows" % (fi, p_end, rows))
+        if whole:
+            desc.insert(0, "%d whole families" % whole)
         out["cpu_baseline"] = {
             "value": round(sample_rows / t_cpu, 1) if t_cpu > 0 else None, "unit": "rows/s",
             "cores": threads, "kind": "oracle",
-            "sample": "; ".join(desc) + "; scored + cut in %.2f s wall" % t_cpu}
+            "sample": "; ".join(desc) + " (%d rows); scored + cut in %.2f s wall" % (sample_rows, t_cpu)}
     print(json.dumps(out))
 
 
