@@ -257,6 +257,8 @@ __device__ __forceinline__ void rank_walk_n(int count, int g, int depth, uint32_
 }
 
 constexpr int kRankThreads = 64 * kRankWaves;
+constexpr int kRankTileBatch = 11;   // 16-byte loads in flight per thread while tiles are fetched
+                                     // (six 164-feature rank tiles are 10.25 pieces per thread)
 
 template <bool DUMP>
 __global__ void __launch_bounds__(kRankThreads)
@@ -306,13 +308,13 @@ traverse_rank_kernel(const FamDesc *__restrict__ descs, int n_families)
         auto src = FS_GLOBAL(const u32x4, d.ranks + (int64_t)tile_first * F * 64);
         const int per_tile = F * 8;                        // 16-byte pieces per tile
         const int n16 = tiles_here * per_tile;
-        for (int base = tid; base < n16; base += 4 * kRankThreads) {
-            u32x4 t4[4];
+        for (int base = tid; base < n16; base += kRankTileBatch * kRankThreads) {
+            u32x4 t4[kRankTileBatch];
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < kRankTileBatch; ++q)
                 t4[q] = src[min(base + q * kRankThreads, n16 - 1)];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < kRankTileBatch; ++q) {
                 const int i = base + q * kRankThreads;
                 if (i < n16)
                     lds_store_u4(tile0 + 16u * (uint32_t)i, t4[q]);   // tiles are contiguous in LDS too
@@ -339,17 +341,26 @@ traverse_rank_kernel(const FamDesc *__restrict__ descs, int n_families)
     }
     const uint32_t val_stride = (uint32_t)T * 256u;
 
+    // Wavefronts 0..T-1 do the ordered sums.  When the others can carry a whole chunk in their
+    // prefetch registers they copy it alone, so a sum and the copy run side by side.
+    const int n_copiers = kRankThreads - 64 * T;
     for (int c = 0; c < n_chunks; ++c) {
         const int first = c * per_chunk;
         const int n = uniform(min(per_chunk, n_trees - first));
-        int n_next = 0;
+        int n_next = 0, cp_id = tid, cp_n = kRankThreads;
         if (c + 1 < n_chunks) {                            // next chunk: global -> registers
             n_next = min(per_chunk, n_trees - first - per_chunk);
             const int n16 = n_next * tree16;
             auto src = image + (int64_t)(first + per_chunk) * tree16;
+            if (n16 <= kRankPrefetchRegs * n_copiers) {
+                cp_n = n_copiers;
+                cp_id = tid - 64 * T;                      // negative in the summing wavefronts
+            }
+            if (cp_id >= 0) {
 #pragma unroll
-            for (int j = 0; j < kRankPrefetchRegs; ++j)
-                pf[j] = src[min(tid + j * kRankThreads, n16 - 1)];
+                for (int j = 0; j < kRankPrefetchRegs; ++j)
+                    pf[j] = src[min(cp_id + j * cp_n, n16 - 1)];
+            }
         }
         const uint32_t val0 = tile0 - (uint32_t)per_chunk * val_stride;   // fixed: above any image
         if (active) {
@@ -386,11 +397,13 @@ traverse_rank_kernel(const FamDesc *__restrict__ descs, int n_families)
         }
         if (c + 1 < n_chunks) {
             const int n16 = n_next * tree16;
+            if (cp_id >= 0) {
 #pragma unroll
-            for (int j = 0; j < kRankPrefetchRegs; ++j) {
-                const int i = tid + j * kRankThreads;
-                if (i < n16)
-                    lds_store_u4(16u * (uint32_t)i, pf[j]);
+                for (int j = 0; j < kRankPrefetchRegs; ++j) {
+                    const int i = cp_id + j * cp_n;
+                    if (i < n16)
+                        lds_store_u4(16u * (uint32_t)i, pf[j]);
+                }
             }
             __syncthreads();
         }

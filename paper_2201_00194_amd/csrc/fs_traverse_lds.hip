@@ -28,6 +28,8 @@
 
 namespace fs {
 
+constexpr int kTileBatch = 8;    // 16-byte loads in flight per thread while tiles are fetched
+
 // Walk K trees of the current chunk for this lane's row.  root[k] are LDS byte offsets; on
 // return a[k] is the LDS offset of the leaf reached and v[k] its value.
 // COMPACT: perfect trees with 4-byte leaves, so the last split level steps by 4.
@@ -160,13 +162,14 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
         auto src = FS_GLOBAL(const u32x4, d.features + (int64_t)tile_first * F * 64);
         const int per_tile = F * 16;                       // 16-byte pieces per tile
         const int n16 = tiles_here * per_tile;
-        for (int base = tid; base < n16; base += 4 * kLdsThreads) {
-            u32x4 t4[4];
+        // two tiles are 7 pieces per thread: one batch, one exposure of the HBM latency
+        for (int base = tid; base < n16; base += kTileBatch * kLdsThreads) {
+            u32x4 t4[kTileBatch];
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < kTileBatch; ++q)
                 t4[q] = src[min(base + q * kLdsThreads, n16 - 1)];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < kTileBatch; ++q) {
                 const int i = base + q * kLdsThreads;
                 if (i < n16) {
                     const int t = i / per_tile, j = i - t * per_tile;
@@ -200,16 +203,25 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
     const int n_chunks = d.n_chunks;
     const uint32_t val_stride = (uint32_t)T * 256u;        // bytes between trees' value rows
 
+    // Wavefronts 0..T-1 do the ordered sums.  When the others can carry a whole chunk in their
+    // prefetch registers they copy it alone, so a sum and the copy run side by side.
+    const int n_copiers = kLdsThreads - 64 * T;
     for (int c = 0; c < n_chunks; ++c) {
         ChunkHdr hn = h;
-        int n16_next = 0;
+        int n16_next = 0, cp_id = tid, cp_n = kLdsThreads;
         if (c + 1 < n_chunks) {                            // next chunk: global -> registers
             hn = *FS_CONST(ChunkHdr, d.chunks + c + 1);
             auto src = FS_GLOBAL(const u32x4, d.image + hn.byte_off);
             n16_next = (int)(hn.bytes >> 4);
+            if (n16_next <= kPrefetchRegs * n_copiers) {
+                cp_n = n_copiers;
+                cp_id = tid - 64 * T;                      // negative in the summing wavefronts
+            }
+            if (cp_id >= 0) {
 #pragma unroll
-            for (int j = 0; j < kPrefetchRegs; ++j)
-                pf[j] = src[min(tid + j * kLdsThreads, n16_next - 1)];
+                for (int j = 0; j < kPrefetchRegs; ++j)
+                    pf[j] = src[min(cp_id + j * cp_n, n16_next - 1)];
+            }
         }
         const int n = uniform((int)h.n_trees);
         const int depth = uniform((int)h.depth);
@@ -256,11 +268,13 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
             // summed right now (only when chunk sizes differ a lot): then wait for the readers.
             if (16u * (uint32_t)n16_next > val0)
                 __syncthreads();
+            if (cp_id >= 0) {
 #pragma unroll
-            for (int j = 0; j < kPrefetchRegs; ++j) {
-                const int i = tid + j * kLdsThreads;
-                if (i < n16_next)
-                    lds_store_u4(16u * (uint32_t)i, pf[j]);
+                for (int j = 0; j < kPrefetchRegs; ++j) {
+                    const int i = cp_id + j * cp_n;
+                    if (i < n16_next)
+                        lds_store_u4(16u * (uint32_t)i, pf[j]);
+                }
             }
             __syncthreads();
         }
