@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3, help="workload 0..4")
+    ap.add_argument("--foresee", action="store_true",
+                    help="instead of --config: the family-scoped step of Algorithm 1 (many small "
+                         "pools per family model, k = 16)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debug only)")
     ap.add_argument("--trees", type=int, default=None, help="override trees per family (debug only)")
@@ -123,9 +126,13 @@ def main():
     torch.cuda.set_device(0)
 
     t0 = time.time()
-    case = W.make_case(args.config, seed=args.seed, scale=args.scale, trees=args.trees)
+    if args.foresee:
+        case = W.make_foresee_case(seed=args.seed, scale=args.scale,
+                                   **({"trees": args.trees} if args.trees else {}))
+    else:
+        case = W.make_case(args.config, seed=args.seed, scale=args.scale, trees=args.trees)
     gen_s = time.time() - t0
-    devs = [api.DeviceFamily(f, layout=api.FS_COLBLOCK64) for f in case.families]
+    devs = api.upload_case(case, layout=api.FS_COLBLOCK64)
     fams = api.PreparedFamilies([d.family() for d in devs])
     reqs = api.PreparedTopk([d.topk_request() for d in devs])
     n_rows, n_prog = case.n_rows, case.n_programs
@@ -174,12 +181,12 @@ def main():
              "traverse_global_kernel": prof["traverse_global"]}
     kname = max(cands, key=lambda k: cands[k][0])
     trav_ms, trav_n = cands[kname]
-    model_bytes = sum(8 * f.model.n_nodes for f in case.families)
+    model_bytes = sum(8 * m.n_nodes for m in {id(f.model): f.model for f in case.families}.values())
     alg_bytes = sum(f.n_rows * (f.model.n_features * 4 + 4) for f in case.families) + model_bytes
     trav_avg_ms = trav_ms / max(1, trav_n)
     achieved = alg_bytes / (trav_avg_ms * 1e-3) / 1e9 if trav_avg_ms > 0 else 0.0
     roofline = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": recorded_traffic(args.config),
+                "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None if args.foresee else recorded_traffic(args.config),
                 "kernel": kname, "kernel_avg_ms": round(trav_avg_ms, 5),
                 "algorithmic_bytes_per_launch": int(alg_bytes)}
 
@@ -196,7 +203,8 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "configs[%d] %s" % (args.config, case.name), "seed": args.seed,
+        "config": {"workload": ("foresee step (Algorithm 1, family scope) %s" % case.name) if args.foresee
+                   else "configs[%d] %s" % (args.config, case.name), "seed": args.seed,
                    "scale": args.scale, "trees_override": args.trees, "families": len(case.families), "rows": n_rows,
                    "programs": n_prog, "feature_layout": "colblock64",
                    "feature_bytes": int(case.feature_bytes)},

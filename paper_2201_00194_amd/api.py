@@ -238,14 +238,28 @@ def fs_profile_end() -> dict:
 
 # ---- conveniences for tests and the benchmark (allocation + marshalling only) ---------------
 
+def upload_case(case, layout: int = FS_COLBLOCK64, **kw):
+    """One `DeviceFamily` per entry of `case.families`; entries that share a host `Model`
+    object share one `fs_model`."""
+    models, out = {}, []
+    for f in case.families:
+        key = id(f.model)
+        if key not in models:
+            models[key] = fs_model.from_arrays(f.model)
+        out.append(DeviceFamily(f, layout=layout, model=models[key], **kw))
+    return out
+
+
 class DeviceFamily:
     """Uploads one `workloads.Family` and allocates its outputs."""
 
     def __init__(self, fam, layout: int = FS_COLBLOCK64, device: str = "cuda:0",
-                 want_row_score: bool = False, want_leaf_idx: bool = False):
+                 want_row_score: bool = False, want_leaf_idx: bool = False, model=None):
+        """`model`: an existing `fs_model` to use (families that share a cost model) instead
+        of building one from `fam.model`."""
         dev = torch.device(device)
         self.host = fam
-        self.model = fs_model.from_arrays(fam.model)
+        self.model = model if model is not None else fs_model.from_arrays(fam.model)
         self.n_rows, self.n_programs, self.k = fam.n_rows, fam.n_programs, fam.k
         x = torch.from_numpy(np.ascontiguousarray(fam.features)).to(dev)
         if x.numel() == 0:

@@ -335,6 +335,36 @@ def make_case(cfg: int, seed: int = 0, scale: float = 1.0, trees: Optional[int] 
     raise ValueError(f"unknown config {cfg}")
 
 
+def make_foresee_case(seed: int = 0, scale: float = 1.0, families: int = 12,
+                      trees: int = 200, depth: int = 8, early_leaf_q: float = 0.2,
+                      k: int = 16) -> Case:
+    """The family-scoped step of the paper's Algorithm 1 as one batch: every family's single
+    model scores the candidate pools of its member subgraphs and g*p = 16 candidates per
+    subgraph go on (Section 4.2, p = 0.25, g = 64).
+
+    `families` families of 2..6 member subgraphs (Table 1 of the paper: 9-38 subgraphs per
+    network); a pool holds 320..4288 programs (the pool sizes of the Section 3.2 example) of
+    1..32 statements; models and features as in the power-law workload (irregular trees of
+    depth <= 8, 50 % exact zeros).  The entries of `Case.families` are the pools; pools of one
+    family share one `Model` object, which is drawn from the first pool's rows.
+    """
+    rng = np.random.default_rng([seed, 1001])
+    case = Case(name="foresee_step", seed=seed,
+                notes=f"foresee step: {families} families x 2..6 pools of 320..4288 programs, "
+                      f"k={k}; scale={scale}, trees={trees}")
+    for _ in range(families):
+        members = int(rng.integers(2, 7))
+        model = None
+        for _ in range(members):
+            n_prog = _scaled(int(rng.integers(320, 4289)), scale, floor=4)
+            off = uniform_prog_off(rng, n_prog, 1, 32)
+            X = draw_features(rng, int(off[-1]), 0.5)
+            if model is None:
+                model = draw_model(rng, X, trees, depth, early_leaf_q=early_leaf_q)
+            case.families.append(Family(model, X, off, k))
+    return case
+
+
 def make_small_family(seed: int, n_programs: int, stmts: Tuple[int, int], n_trees: int,
                       depth: int, early_leaf_q: float = 0.0, zero_frac: float = 0.3,
                       n_features: int = N_FEATURES, k: int = 16, bias: float = 0.0,

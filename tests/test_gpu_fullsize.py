@@ -26,7 +26,7 @@ def api():
 
 def run_case(api, case):
     import torch
-    devs = [api.DeviceFamily(f, layout=api.FS_COLBLOCK64) for f in case.families]
+    devs = api.upload_case(case, layout=api.FS_COLBLOCK64)
     api.fs_score_families(api.PreparedFamilies([d.family() for d in devs]))
     api.fs_topk(api.PreparedTopk([d.topk_request() for d in devs]))
     torch.cuda.synchronize()
@@ -119,3 +119,16 @@ def test_cfg4_full_size_every_program(api, oracle):
             check_full(oracle, f, d)
         else:
             check_sample(oracle, f, d.prog_score.cpu().numpy()[: f.n_programs], 60, 40 + i)
+
+
+def test_foresee_step_full_size_every_program(api, oracle):
+    """The family-scoped step of Algorithm 1 at the size `bench.py --foresee` times: every
+    pool of every family scored by the family's shared model and cut to 16, all compared with
+    the oracle (about 0.9 M rows)."""
+    case = W.make_foresee_case(seed=0)
+    assert len({id(f.model) for f in case.families}) == 12
+    devs = run_case(api, case)
+    assert len({id(d.model) for d in devs}) == 12        # one fs_model per family
+    for fam, dev in zip(case.families, devs):
+        check_cut_properties(oracle, fam, dev)
+        check_full(oracle, fam, dev)

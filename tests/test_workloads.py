@@ -89,3 +89,15 @@ def test_cfg1_cfg2_scaled_shapes():
     assert c1.families[0].model.n_nodes == 5 * 511
     c2 = W.make_case(2, seed=0, scale=0.001, trees=3)
     assert c2.families[0].n_rows == 262 * 8 and c2.families[0].model.n_nodes == 3 * 2047
+
+
+def test_foresee_case_shape_and_shared_models():
+    case = W.make_foresee_case(seed=3, scale=0.05, trees=5)
+    models = {id(f.model) for f in case.families}
+    assert len(models) == 12 and 24 <= len(case.families) <= 72
+    for f in case.families:
+        assert f.k == 16 and f.prog_off[0] == 0 and f.prog_off[-1] == f.n_rows
+        assert np.all(np.diff(f.prog_off) >= 1) and np.all(np.diff(f.prog_off) <= 32)
+        assert f.features.shape == (f.n_rows, 164) and f.model.n_trees == 5
+    again = W.make_foresee_case(seed=3, scale=0.05, trees=5)
+    assert all(np.array_equal(a.features, b.features) for a, b in zip(case.families, again.families))
