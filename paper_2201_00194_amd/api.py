@@ -20,6 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libfamilyseer.so")
 FS_OK, FS_EINVAL, FS_ENOMEM, FS_EDEVICE, FS_EUNSUPPORTED = 0, -1, -2, -3, -4
 FS_ROWMAJOR, FS_COLBLOCK64 = 0, 1
 FS_MAX_TOPK = 16384
+FS_MAX_FEATURES = 4096
+FS_MAX_TREE_NODES = 65535
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(

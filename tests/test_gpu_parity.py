@@ -382,3 +382,38 @@ def test_foresee_step_shape_many_small_pools_sharing_a_family_model(api, oracle)
     for f, d in zip(host, devs):
         check_family(oracle, f, d)
     assert len(shared) == 5 and len(devs) >= 15
+
+
+def test_maximum_sizes_of_the_interface(api, oracle):
+    """The documented limits themselves: FS_MAX_FEATURES columns, a tree of FS_MAX_TREE_NODES
+    nodes (leaf ids up to 65534), one program holding 100 000 rows next to one-row programs,
+    and just past each limit an error instead of a launch."""
+    import torch
+    wide = W.make_small_family(seed=61, n_programs=40, stmts=(1, 5), n_trees=6, depth=5,
+                               n_features=api.FS_MAX_FEATURES, k=7)
+    deep = W.make_small_family(seed=62, n_programs=300, stmts=(1, 3), n_trees=2, depth=15,
+                               n_features=20, k=11)
+    assert int(np.diff(deep.model.tree_off).max()) == api.FS_MAX_TREE_NODES
+    long_ = W.make_small_family(seed=63, n_programs=3, stmts=(1, 1), n_trees=9, depth=4,
+                                n_features=32, k=3)
+    rng = np.random.default_rng(64)
+    long_.features = W.draw_features(rng, 100_002, 0.3, n_features=32)
+    long_.prog_off = np.array([0, 1, 100_001, 100_002], np.int32)
+    fams = [wide, deep, long_]
+    for layout in LAYOUTS:
+        devs = [api.DeviceFamily(f, layout=layout, want_row_score=True, want_leaf_idx=True)
+                for f in fams]
+        api.fs_score_families([d.family() for d in devs])
+        api.fs_topk([d.topk_request() for d in devs])
+        torch.cuda.synchronize()
+        for f, d in zip(fams, devs):
+            check_family(oracle, f, d)
+    # one past the limits
+    m = wide.model
+    with pytest.raises(api.FsError):
+        api.fs_model.from_arrays(W.Model(api.FS_MAX_FEATURES + 1, m.tree_off, m.split_feature,
+                                         m.threshold, m.left, m.right, m.value, 0.0))
+    big = W.make_small_family(seed=65, n_programs=1, stmts=(1, 1), n_trees=1, depth=16,
+                              n_features=8, k=1)
+    with pytest.raises(api.FsError):
+        api.fs_model.from_arrays(big.model)
