@@ -365,6 +365,70 @@ def make_foresee_case(seed: int = 0, scale: float = 1.0, families: int = 12,
     return case
 
 
+def draw_cuts(X: np.ndarray, max_cuts: int = 255) -> Tuple[np.ndarray, np.ndarray]:
+    """Candidate thresholds for histogram training: per column, at most `max_cuts` of its
+    distinct values (never the smallest, which nothing lies below), evenly spaced in rank
+    when there are more.  Returns (cut_off [D+1] int32, cuts float32), ascending per column."""
+    off = [0]
+    out = []
+    for j in range(X.shape[1]):
+        u = np.unique(X[:, j])
+        u = u[~np.isnan(u)][1:]
+        if u.shape[0] > max_cuts:
+            pick = np.unique(np.round(np.linspace(0, u.shape[0] - 1, max_cuts)).astype(np.int64))
+            u = u[pick]
+        out.append(u.astype(np.float32))
+        off.append(off[-1] + u.shape[0])
+    cuts = np.concatenate(out) if out else np.zeros(0, np.float32)
+    return np.asarray(off, np.int32), cuts.astype(np.float32)
+
+
+@dataclass
+class TrainSet:
+    """Measured programs of one family: what train_cost_model of Algorithm 1 receives."""
+    features: np.ndarray   # float32 [R, D] row-major
+    prog_off: np.ndarray   # int32 [P+1]
+    target: np.ndarray     # float32 [P]
+    cut_off: np.ndarray    # int32 [D+1]
+    cuts: np.ndarray       # float32
+
+    @property
+    def n_rows(self) -> int:
+        return int(self.features.shape[0])
+
+    @property
+    def n_programs(self) -> int:
+        return int(self.prog_off.shape[0] - 1)
+
+
+def make_train_set(seed: int, n_programs: int, stmts: Tuple[int, int] = (1, 16),
+                   n_features: int = N_FEATURES, zero_frac: float = 0.3, max_cuts: int = 255,
+                   teacher_trees: int = 20, teacher_depth: int = 4, noise: float = 0.02) -> TrainSet:
+    """Synthetic measured programs: features as in the scoring workloads, targets = the
+    program score of a hidden random ensemble plus Gaussian noise (so there is something to
+    learn), rounded to float32."""
+    rng = np.random.default_rng([seed, 4242])
+    lo, hi = stmts
+    off = uniform_prog_off(rng, n_programs, lo, hi) if hi > lo else fixed_prog_off(n_programs, lo)
+    X = draw_features(rng, int(off[-1]), zero_frac, n_features=n_features)
+    teacher = draw_model(rng, X, teacher_trees, teacher_depth)
+    # the teacher's row outputs, by direct table walk over the full trees (heap order)
+    rows = np.zeros(X.shape[0], np.float64)
+    for t in range(teacher.n_trees):
+        o = int(teacher.tree_off[t])
+        node = np.zeros(X.shape[0], np.int64)
+        for _ in range(teacher_depth):
+            f = teacher.split_feature[o + node]
+            thr = teacher.threshold[o + node]
+            x = X[np.arange(X.shape[0]), f]
+            node = np.where(x < thr, teacher.left[o + node], teacher.right[o + node])
+        rows += teacher.value[o + node]
+    y = np.add.reduceat(rows, off[:-1].astype(np.int64)) if n_programs else np.zeros(0)
+    y = y + rng.normal(0.0, noise, size=n_programs)
+    cut_off, cuts = draw_cuts(X, max_cuts)
+    return TrainSet(X, off, y.astype(np.float32), cut_off, cuts)
+
+
 def make_small_family(seed: int, n_programs: int, stmts: Tuple[int, int], n_trees: int,
                       depth: int, early_leaf_q: float = 0.0, zero_frac: float = 0.3,
                       n_features: int = N_FEATURES, k: int = 16, bias: float = 0.0,
