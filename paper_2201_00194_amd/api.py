@@ -289,3 +289,111 @@ class DeviceFamily:
 
     def topk_request(self) -> TopkRequest:
         return TopkRequest(self.prog_score, self.n_programs, self.k, self.topk_idx, self.topk_score)
+
+
+# ---- training (familyseer_train.h) -------------------------------------------------------------
+
+FS_TRAIN_MAX_DEPTH = 8
+FS_TRAIN_MAX_CUTS = 255
+
+
+class _FsTrainParams(ctypes.Structure):
+    _fields_ = [("max_depth", ctypes.c_int32), ("eta", ctypes.c_float), ("lam", ctypes.c_float),
+                ("min_gain", ctypes.c_float), ("min_child_weight", ctypes.c_float),
+                ("grad_scale", ctypes.c_float)]
+
+
+_lib.fs_trainer_create.restype = ctypes.c_int
+_lib.fs_trainer_create.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32, ctypes.c_void_p,
+                                   ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32,
+                                   ctypes.c_void_p, _i32p, _f32p, ctypes.c_float, ctypes.c_int32,
+                                   ctypes.c_int32, ctypes.c_void_p]
+_lib.fs_trainer_destroy.restype = None
+_lib.fs_trainer_destroy.argtypes = [ctypes.c_void_p]
+_lib.fs_train_boost.restype = ctypes.c_int
+_lib.fs_train_boost.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32,
+                                ctypes.POINTER(_FsTrainParams), ctypes.c_void_p]
+_lib.fs_trainer_size.restype = ctypes.c_int
+_lib.fs_trainer_size.argtypes = [ctypes.c_void_p, _i32p, ctypes.POINTER(ctypes.c_int64), ctypes.c_void_p]
+_lib.fs_trainer_export.restype = ctypes.c_int
+_lib.fs_trainer_export.argtypes = [ctypes.c_void_p, _i32p, _i32p, _f32p, _i32p, _i32p, _f32p,
+                                   ctypes.c_void_p]
+_lib.fs_trainer_predictions.restype = ctypes.c_int
+_lib.fs_trainer_predictions.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+
+
+def train_params(max_depth: int = 6, eta: float = 0.3, lam: float = 1.0, min_gain: float = 0.0,
+                 min_child_weight: float = 1.0, grad_scale: float = float(1 << 20)) -> _FsTrainParams:
+    return _FsTrainParams(max_depth, eta, lam, min_gain, min_child_weight, grad_scale)
+
+
+class fs_trainer:
+    """Owner of one `fs_trainer*`: a family's measured programs, binned, and the model so far."""
+
+    def __init__(self, n_features: int, features: torch.Tensor, layout: int, n_rows: int,
+                 prog_off: torch.Tensor, n_programs: int, target: torch.Tensor, cut_off, cuts,
+                 bias: float = 0.0, max_depth: int = 6, max_trees: int = 64,
+                 stream: Optional[torch.cuda.Stream] = None):
+        co = np.ascontiguousarray(cut_off, dtype=np.int32)
+        cu = np.ascontiguousarray(cuts, dtype=np.float32)
+        if cu.size == 0:
+            cu = np.zeros(1, np.float32)
+        self.handle = ctypes.c_void_p()
+        self.n_features, self.n_rows, self.n_programs, self.bias = n_features, n_rows, n_programs, bias
+        _check(_lib.fs_trainer_create(ctypes.byref(self.handle), n_features, _ptr(features), layout,
+                                      n_rows, _ptr(prog_off), n_programs, _ptr(target),
+                                      co.ctypes.data_as(_i32p), cu.ctypes.data_as(_f32p), bias,
+                                      max_depth, max_trees, _stream_ptr(stream)))
+
+    @classmethod
+    def from_train_set(cls, ts, layout: int = FS_COLBLOCK64, device: str = "cuda:0", **kw):
+        dev = torch.device(device)
+        x = torch.from_numpy(np.ascontiguousarray(ts.features)).to(dev)
+        if layout == FS_COLBLOCK64:
+            x = fs_pack_colblock64(x, ts.n_rows, ts.features.shape[1])
+        off = torch.from_numpy(np.ascontiguousarray(ts.prog_off, dtype=np.int32)).to(dev)
+        y = torch.from_numpy(np.ascontiguousarray(ts.target, dtype=np.float32)).to(dev)
+        t = cls(ts.features.shape[1], x, layout, ts.n_rows, off, ts.n_programs, y, ts.cut_off,
+                ts.cuts, **kw)
+        torch.cuda.synchronize()          # the inputs may be freed once they are binned
+        return t
+
+    def size(self, stream: Optional[torch.cuda.Stream] = None):
+        nt, nn = ctypes.c_int32(), ctypes.c_int64()
+        _check(_lib.fs_trainer_size(self.handle, ctypes.byref(nt), ctypes.byref(nn), _stream_ptr(stream)))
+        return int(nt.value), int(nn.value)
+
+    def export(self, stream: Optional[torch.cuda.Stream] = None):
+        """(tree_off, split_feature, threshold, left, right, value) as numpy arrays."""
+        nt, nn = self.size(stream)
+        to = np.zeros(nt + 1, np.int32)
+        sf, le, ri = (np.zeros(max(1, nn), np.int32) for _ in range(3))
+        th, va = (np.zeros(max(1, nn), np.float32) for _ in range(2))
+        _check(_lib.fs_trainer_export(self.handle, to.ctypes.data_as(_i32p), sf.ctypes.data_as(_i32p),
+                                      th.ctypes.data_as(_f32p), le.ctypes.data_as(_i32p),
+                                      ri.ctypes.data_as(_i32p), va.ctypes.data_as(_f32p),
+                                      _stream_ptr(stream)))
+        return to, sf[:nn], th[:nn], le[:nn], ri[:nn], va[:nn]
+
+    def predictions(self, stream: Optional[torch.cuda.Stream] = None):
+        rows = torch.empty(self.n_rows, dtype=torch.float32, device="cuda")
+        progs = torch.empty(self.n_programs, dtype=torch.float32, device="cuda")
+        _check(_lib.fs_trainer_predictions(self.handle, _ptr(rows), _ptr(progs), _stream_ptr(stream)))
+        return rows, progs
+
+    def destroy(self) -> None:
+        if self.handle:
+            _lib.fs_trainer_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def fs_train_boost(trainers, n_rounds: int, params: _FsTrainParams,
+                   stream: Optional[torch.cuda.Stream] = None) -> None:
+    arr = (ctypes.c_void_p * max(1, len(trainers)))(*[t.handle for t in trainers])
+    _check(_lib.fs_train_boost(len(trainers), arr, n_rounds, ctypes.byref(params), _stream_ptr(stream)))

@@ -4,21 +4,25 @@ import os
 import re
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "familyseer.h")
+HEADERS = [os.path.join(ROOT, "include", n) for n in ("familyseer.h", "familyseer_train.h")]
 LIB = os.path.join(ROOT, "paper_2201_00194_amd", "libfamilyseer.so")
 
 
 def declared_functions():
-    src = open(HEADER).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    names = re.findall(r"\b(fs_[a-z0-9_]+)\s*\(", src)
+    names = []
+    for header in HEADERS:
+        src = open(header).read()
+        src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+        names += re.findall(r"\b(fs_[a-z0-9_]+)\s*\(", src)
     return sorted(set(names))
 
 
 def test_header_declares_the_named_entry_points():
     names = declared_functions()
     for must in ("fs_score_families", "fs_topk", "fs_model_create", "fs_model_destroy",
-                 "fs_pack_colblock64", "fs_last_error", "fs_version"):
+                 "fs_pack_colblock64", "fs_last_error", "fs_version", "fs_trainer_create",
+                 "fs_train_boost", "fs_trainer_export", "fs_trainer_predictions",
+                 "fs_trainer_size", "fs_trainer_destroy"):
         assert must in names
 
 
@@ -28,7 +32,7 @@ def test_library_exports_every_declared_symbol():
         build.build()
     lib = ctypes.CDLL(LIB)
     for name in declared_functions():
-        assert hasattr(lib, name), f"{name} declared in familyseer.h but not exported"
+        assert hasattr(lib, name), f"{name} declared in include/*.h but not exported"
     lib.fs_version.restype = ctypes.c_int
     assert lib.fs_version() >= 100
     lib.fs_last_error.restype = ctypes.c_char_p

@@ -1,0 +1,126 @@
+"""GPU training of family cost models against the training oracle: the trees (every array,
+bit for bit) and the predictions on the training set, through the C ABI
+(`fs_trainer_create`, `fs_train_boost`, `fs_trainer_export`, `fs_trainer_predictions`)."""
+import numpy as np
+import pytest
+
+from paper_2201_00194_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2201_00194_amd import api as A
+    return A
+
+
+@pytest.fixture(scope="module")
+def T():
+    from oracle import train_oracle
+    train_oracle.build()
+    return train_oracle
+
+
+def same_trees(got, exp):
+    to, sf, th, le, ri, va = got
+    assert np.array_equal(to, exp.tree_off)
+    assert np.array_equal(sf, exp.split_feature)
+    assert np.array_equal(le, exp.left) and np.array_equal(ri, exp.right)
+    assert np.array_equal(th.view(np.uint32), exp.threshold.view(np.uint32))
+    assert np.array_equal(va.view(np.uint32), exp.value.view(np.uint32))
+
+
+def check(api, T, ts, rounds, layout=1, bias=0.0, **kw):
+    import torch
+    p = api.train_params(**kw)
+    tr = api.fs_trainer.from_train_set(ts, layout=layout, bias=bias, max_depth=p.max_depth,
+                                       max_trees=rounds)
+    api.fs_train_boost([tr], rounds, p)
+    torch.cuda.synchronize()
+    exp = T.train(ts.features, ts.prog_off, ts.target, ts.cut_off, ts.cuts, bias=bias,
+                  n_rounds=rounds, max_depth=p.max_depth, eta=p.eta, lam=p.lam, min_gain=p.min_gain,
+                  min_child_weight=p.min_child_weight, grad_scale=p.grad_scale)
+    same_trees(tr.export(), exp)
+    rows, progs = tr.predictions()
+    torch.cuda.synchronize()
+    assert np.array_equal(rows.cpu().numpy().view(np.uint32), exp.row_pred.view(np.uint32))
+    assert np.array_equal(progs.cpu().numpy().view(np.uint32), exp.prog_pred.view(np.uint32))
+    return tr, exp
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_small_family_all_depths(api, T, layout):
+    ts = W.make_train_set(21, 700, stmts=(1, 12), n_features=23, max_cuts=40)
+    for depth in (0, 1, 3, 6):
+        check(api, T, ts, rounds=4, layout=layout, max_depth=depth, eta=0.5, lam=1.0)
+
+
+def test_full_width_features_255_cuts_depth8(api, T):
+    ts = W.make_train_set(22, 1500, stmts=(1, 16), max_cuts=255)
+    ts.features[17, 5] = np.nan
+    ts.features[99, 0] = np.inf
+    check(api, T, ts, rounds=3, max_depth=8, eta=0.3, lam=0.5, bias=0.25)
+
+
+def test_regularisation_and_stopping_rules(api, T):
+    ts = W.make_train_set(23, 400, stmts=(1, 5), n_features=9, max_cuts=15)
+    check(api, T, ts, rounds=3, max_depth=4, eta=1.0, lam=0.0)
+    check(api, T, ts, rounds=3, max_depth=4, eta=0.2, lam=10.0, min_child_weight=40.0)
+    check(api, T, ts, rounds=2, max_depth=4, eta=0.2, lam=1.0, min_gain=5.0)
+    check(api, T, ts, rounds=2, max_depth=3, eta=0.2, lam=1.0, grad_scale=float(1 << 10))
+
+
+def test_batched_families_train_independently(api, T):
+    import torch
+    sets = [W.make_train_set(30 + i, n, stmts=(1, 8), n_features=nf, max_cuts=mc)
+            for i, (n, nf, mc) in enumerate([(300, 12, 20), (1200, 30, 63), (50, 5, 4), (2000, 12, 255)])]
+    p = api.train_params(max_depth=5, eta=0.4, lam=1.0)
+    trs = [api.fs_trainer.from_train_set(ts, max_depth=5, max_trees=8) for ts in sets]
+    api.fs_train_boost(trs, 3, p)
+    api.fs_train_boost(trs[:2], 2, p)                 # the first two get two more rounds
+    torch.cuda.synchronize()
+    for i, (ts, tr) in enumerate(zip(sets, trs)):
+        exp = T.train(ts.features, ts.prog_off, ts.target, ts.cut_off, ts.cuts,
+                      n_rounds=5 if i < 2 else 3, max_depth=5, eta=0.4, lam=1.0)
+        same_trees(tr.export(), exp)
+        assert tr.size()[0] == (5 if i < 2 else 3)
+
+
+def test_trained_model_scores_identically_through_the_scoring_path(api, T, oracle):
+    import torch
+    ts = W.make_train_set(41, 900, stmts=(1, 10), n_features=40, max_cuts=31)
+    tr, exp = check(api, T, ts, rounds=10, max_depth=5, eta=0.3, lam=1.0, bias=0.5)
+    to, sf, th, le, ri, va = tr.export()
+    host = W.Model(40, to, sf, th, le, ri, va, 0.5)
+    fam = W.Family(host, ts.features, ts.prog_off, 16)
+    dev = api.DeviceFamily(fam, want_row_score=True)
+    api.fs_score_families([dev.family()])
+    torch.cuda.synchronize()
+    rows, progs = tr.predictions()
+    assert torch.equal(dev.row_score[: ts.n_rows], rows)
+    assert torch.equal(dev.prog_score[: ts.n_programs], progs)
+    assert exp.loss[-1] < 0.5 * exp.loss[0]
+
+
+def test_errors(api):
+    import torch
+    ts = W.make_train_set(51, 40, stmts=(1, 3), n_features=4, max_cuts=7)
+    tr = api.fs_trainer.from_train_set(ts, max_depth=3, max_trees=2)
+    with pytest.raises(api.FsError):
+        api.fs_train_boost([tr], 1, api.train_params(max_depth=4))          # deeper than created for
+    with pytest.raises(api.FsError):
+        api.fs_train_boost([tr], 3, api.train_params(max_depth=3))          # more trees than room
+    with pytest.raises(api.FsError):
+        api.fs_train_boost([tr], 1, api.train_params(max_depth=3, grad_scale=3.0))
+    with pytest.raises(api.FsError):
+        api.fs_train_boost([tr, tr], 1, api.train_params(max_depth=3))
+    bad = W.make_train_set(52, 40, stmts=(1, 3), n_features=4, max_cuts=7)
+    bad.cuts = bad.cuts[::-1].copy()
+    with pytest.raises(api.FsError):
+        api.fs_trainer.from_train_set(bad, max_depth=3, max_trees=2)
+    api.fs_train_boost([tr], 2, api.train_params(max_depth=3))              # still works
+    torch.cuda.synchronize()
+    assert tr.size()[0] == 2
