@@ -39,6 +39,11 @@ def parse():
     ap.add_argument("--foresee", action="store_true",
                     help="instead of --config: the family-scoped step of Algorithm 1 (many small "
                          "pools per family model, k = 16)")
+    ap.add_argument("--train", action="store_true",
+                    help="instead of scoring: boosting rounds of the family models on synthetic "
+                         "measured programs (train_cost_model of Algorithm 1); a step is one round "
+                         "for all families")
+    ap.add_argument("--depth", type=int, default=6, help="--train: tree depth")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debug only)")
     ap.add_argument("--trees", type=int, default=None, help="override trees per family (debug only)")
@@ -110,6 +115,73 @@ def mean_path_length(case, sample_rows: int = 512):
     return (tot / max(1, cnt), lock / max(1, cnt), cnt)
 
 
+def train_main(args, np, torch, api, W):
+    """Boosting rounds for all families of a synthetic tuning job.  value = statement rows
+    taken through one boosting round per second."""
+    t0 = time.time()
+    sets = W.make_train_case(seed=args.seed, scale=args.scale)
+    gen_s = time.time() - t0
+    total = args.warmup + args.steps
+    prm = api.train_params(max_depth=args.depth, eta=0.2, lam=1.0)
+    trs = [api.fs_trainer.from_train_set(ts, max_depth=args.depth, max_trees=total) for ts in sets]
+    n_rows = sum(ts.n_rows for ts in sets)
+    n_prog = sum(ts.n_programs for ts in sets)
+    n_feat = sets[0].features.shape[1]
+    if args.warmup:
+        api.fs_train_boost(trs, args.warmup, prm)
+    torch.cuda.synchronize()
+    api.fs_profile_begin(16 * args.depth * args.steps + 64)
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    w0 = time.perf_counter()
+    e0.record()
+    api.fs_train_boost(trs, args.steps, prm)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - w0) * 1e3
+    prof = api.fs_profile_end()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    # dominant kernel: the histogram build.  Algorithmic bytes per launch (one level): every
+    # bin once (1 B per row and feature) plus gradient, curvature and node of every row once.
+    hist_ms, hist_n = prof["train_hist"]
+    alg_bytes = n_rows * (n_feat + 10)
+    hist_avg = hist_ms / max(1, hist_n)
+    achieved = alg_bytes / (hist_avg * 1e-3) / 1e9 if hist_avg > 0 else 0.0
+    out = {
+        "metric": "statement-rows per boosting round per second (family cost-model training)",
+        "value": round(n_rows / (ms_per_step * 1e-3), 1), "unit": "rows/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64+f64",
+        "data": "synthetic",
+        "config": {"workload": "training: %d families, depth %d, 255 cuts per feature" %
+                               (len(sets), args.depth), "seed": args.seed, "scale": args.scale,
+                   "rows": n_rows, "programs": n_prog, "features": n_feat},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                     "kernel": "train_zero_hist_kernel+train_hist_kernel (one level)",
+                     "kernel_avg_ms": round(hist_avg, 5),
+                     "algorithmic_bytes_per_launch": int(alg_bytes)},
+        "kernels_ms_per_step": {k: round(v[0] / max(1, args.steps), 5) for k, v in prof.items()
+                                if k.startswith("train")},
+        "host_wall_ms_per_step": round(wall_ms / args.steps, 5),
+        "workload_gen_s": round(gen_s, 2),
+    }
+    if not args.no_cpu_baseline:
+        from oracle import train_oracle as TO
+        TO.build()
+        ts = min(sets, key=lambda s: s.n_rows)
+        rounds = 2
+        c0 = time.perf_counter()
+        TO.train(ts.features, ts.prog_off, ts.target, ts.cut_off, ts.cuts, n_rounds=rounds,
+                 max_depth=args.depth, eta=0.2, lam=1.0)
+        t_cpu = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": round(ts.n_rows * rounds / t_cpu, 1), "unit": "rows/s",
+                               "cores": 1, "kind": "oracle",
+                               "sample": "smallest family (%d rows), %d rounds in %.2f s wall"
+                                         % (ts.n_rows, rounds, t_cpu)}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -124,6 +196,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.train:
+        return train_main(args, np, torch, api, W)
 
     t0 = time.time()
     if args.foresee:

@@ -182,7 +182,10 @@ enum { FS_KERNEL_TRAVERSE = 0,        /* LDS-staged traversal (the hot kernel)  
                                          the LDS kernel does not take)                       */
        FS_KERNEL_RANK_CODE = 5,       /* features -> 16-bit ranks (deep perfect-tree models)  */
        FS_KERNEL_TRAVERSE_RANK = 6,   /* LDS-staged traversal over rank-coded features        */
-       FS_KERNEL_CLASSES = 7 };
+       FS_KERNEL_TRAIN_HIST = 7,      /* training: gradient histograms (familyseer_train.h)   */
+       FS_KERNEL_TRAIN_SPLIT = 8,     /* training: best cut per (node, feature), node decision */
+       FS_KERNEL_TRAIN_OTHER = 9,     /* training: gradients, row moves, output update, emit  */
+       FS_KERNEL_CLASSES = 10 };
 
 /*
  * Between fs_profile_begin and fs_profile_end the library brackets every kernel group it

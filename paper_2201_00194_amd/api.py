@@ -77,7 +77,7 @@ _lib.fs_profile_begin.argtypes = [ctypes.c_int32]
 _lib.fs_profile_end.restype = ctypes.c_int
 _lib.fs_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), _i32p]
 KERNEL_CLASSES = ("traverse", "segsum", "topk", "pack", "traverse_global", "rank_code",
-                  "traverse_rank")
+                  "traverse_rank", "train_hist", "train_split", "train_other")
 
 
 def _check(rc: int) -> None:

@@ -202,7 +202,8 @@ int launch_pack_colblock64(const float *in, int64_t n_rows, int32_t n_features, 
 // ---- optional per-kernel timing (fs_profile_begin / fs_profile_end) ----------------------------
 enum KernelClass { kKernTraverse = 0, kKernSegsum = 1, kKernTopk = 2, kKernPack = 3,
                    kKernTraverseGlobal = 4, kKernRankCode = 5, kKernTraverseRank = 6,
-                   kKernClasses = 7 };
+                   kKernTrainHist = 7, kKernTrainSplit = 8, kKernTrainOther = 9,
+                   kKernClasses = 10 };
 // Records an event pair around the launches made between prof_start and prof_stop when
 // profiling is on; no-ops otherwise.  Both run under the API mutex.
 void prof_start(int kernel_class, hipStream_t stream);

@@ -12,9 +12,10 @@
 //   begin_tree   clear the heap of the tree to grow
 //   grad         per program: s_p (row order), g_p, q_p; rows get (q_p, rows of p) and go
 //                back to the root; the root's (G, H) are added up on the way
-//   per level:   zero_hist, hist (LDS histograms per row slab and feature group, flushed
-//                with 64-bit atomics), split (one workgroup per (node, feature): scan the
-//                bins, best cut), pick (per node: best feature, split or leaf, child ids in
+//   per level:   hist (LDS histograms per row slab and feature group, flushed with 64-bit
+//                atomics; a feature's most frequent bin is never counted, it is the node's
+//                total minus the rest), split (one wavefront per (node, feature): scan the
+//                bins, best cut, clear the histogram), pick (per node: best feature, split or leaf, child ids in
 //                breadth-first order), part (rows of split nodes move to a child)
 //   pick         once more at max_depth: what is left becomes leaves
 //   update       row output += value of the row's leaf;  emit: heap -> flat model arrays
@@ -31,18 +32,20 @@ namespace fs {
 constexpr int kHeapNodes = (1 << (FS_TRAIN_MAX_DEPTH + 1)) - 1;   // 511
 constexpr int kBins = FS_TRAIN_MAX_CUTS + 1;                      // 256
 constexpr int kHistThreads = 512;
-constexpr int kHistRowsPerBlock = 4096;
-constexpr int kHistPairs = 32;        // (node, feature) histograms a workgroup keeps in LDS
+constexpr int kHistRowsPerSlab = 65536;
 
 // heap node states
 enum { kAbsent = 0, kOpen = 1, kInternal = 2, kLeaf = 3 };
 
 struct TrainDesc {
-    const uint8_t *bins;       // [feature][r_pad]
+    const uint8_t *bins;       // [feature / 4][r_pad][4]: the bins of four consecutive features
+                               // of a row share one 32-bit word
     const int32_t *prog_off;
     const float *target;
     const int32_t *cut_off;    // device copies of the cut lists
     const float *cuts;
+    const int32_t *hot_bin;    // per feature: its most frequent bin, which no histogram counts
+                               // (it is the node's total minus the other bins)
     float *row_pred;
     float *prog_pred;
     int2 *qh;                  // per row: (gradient in fixed point, curvature)
@@ -99,7 +102,38 @@ train_bin_kernel(const float *__restrict__ x, int layout, int n_features, int n_
     }
     if (v != v)
         lo = m;
-    bins[(int64_t)f * r_pad + r] = (uint8_t)lo;
+    bins[((int64_t)(f >> 2) * r_pad + r) * 4 + (f & 3)] = (uint8_t)lo;
+}
+
+// The most frequent bin of every feature over the whole training set (lowest on ties).
+__global__ void __launch_bounds__(256)
+train_hot_bin_kernel(const uint8_t *__restrict__ bins, int n_rows, int64_t r_pad,
+                     int32_t *__restrict__ hot_bin)
+{
+    __shared__ unsigned int cnt[kBins];
+    __shared__ unsigned int s_best[kBins];
+    __shared__ int s_arg[kBins];
+    const int f = blockIdx.x, t = threadIdx.x;
+    cnt[t] = 0u;
+    __syncthreads();
+    for (int r = t; r < n_rows; r += blockDim.x)
+        atomicAdd(&cnt[bins[((int64_t)(f >> 2) * r_pad + r) * 4 + (f & 3)]], 1u);
+    __syncthreads();
+    s_best[t] = cnt[t];
+    s_arg[t] = t;
+    __syncthreads();
+    for (int off = kBins / 2; off > 0; off >>= 1) {
+        if (t < off) {
+            const unsigned int a = s_best[t], b = s_best[t + off];
+            if (b > a || (b == a && s_arg[t + off] < s_arg[t])) {
+                s_best[t] = b;
+                s_arg[t] = s_arg[t + off];
+            }
+        }
+        __syncthreads();
+    }
+    if (t == 0)
+        hot_bin[f] = s_arg[0];
 }
 
 __global__ void train_fill_kernel(float *p, int64_t n, float v)
@@ -171,62 +205,84 @@ train_grad_kernel(const TrainDesc *__restrict__ descs, float grad_scale, int wit
     }
 }
 
-__global__ void train_zero_hist_kernel(const TrainDesc *__restrict__ descs, int n_slots)
-{
-    const TrainDesc &d = descs[blockIdx.y];
-    const int64_t n = (int64_t)n_slots * d.n_features * kBins * 2;
-    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n;
-         i += (int64_t)gridDim.x * blockDim.x)
-        d.hist[i] = 0ull;
-}
+// Histograms of one level.  A workgroup takes a slab of rows, four consecutive features (one
+// 32-bit word of bins per row) and up to kHistSlots nodes of the level, and keeps their (G, H)
+// histograms in LDS.  blockIdx = (slab, feature group, trainer * passes + pass); a pass covers
+// kHistSlots consecutive nodes.  With one slab per family the histograms are stored as they
+// are; with more they are added to the buffer (which is all zero: the split kernel clears what
+// it reads).
+constexpr int kHistSlots = 8;
 
-// Histograms of one level.  A workgroup takes a slab of rows and `fg` consecutive features
-// and keeps the (G, H) histograms of `slots` nodes x fg features in LDS (at most kHistPairs);
-// blockIdx.z = trainer * passes + pass, a pass covering `slots` consecutive nodes.
 __global__ void __launch_bounds__(kHistThreads)
-train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int fg, int slots, int passes)
+train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, int rows_per_slab,
+                  int n_slabs)
 {
-    extern __shared__ unsigned long long lds_hist[];            // G: [pairs][256] u64
-    unsigned int *lds_h = (unsigned int *)(lds_hist + kHistPairs * kBins);   // H: [pairs][256] u32
+    extern __shared__ unsigned long long lds_hist[];            // G: [pairs][256] u64, then H u32
     const TrainDesc &d = descs[blockIdx.z / passes];
     const int pass = blockIdx.z % passes;
-    const int row0 = blockIdx.x * kHistRowsPerBlock;
-    if (row0 >= d.n_rows)
+    const int row0 = blockIdx.x * rows_per_slab;
+    const int f0 = blockIdx.y * 4;
+    if (row0 >= d.n_rows || f0 >= d.n_features)
         return;
-    const int row1 = min(row0 + kHistRowsPerBlock, d.n_rows);
-    const int f0 = blockIdx.y * fg;
-    const int nf = min(fg, d.n_features - f0);
-    const int node0 = (1 << level) - 1 + pass * slots;          // heap index of slot 0
-    const int pairs = slots * fg;
+    const int row1 = min(row0 + rows_per_slab, d.n_rows);
+    const int nf = min(4, d.n_features - f0);
+    const int n_slots = 1 << level;
+    const int slots = min(kHistSlots, n_slots);
+    const int node0 = n_slots - 1 + pass * slots;               // heap index of slot 0
+    const int pairs = slots * 4;
+    unsigned int *lds_h = (unsigned int *)(lds_hist + pairs * kBins);
     for (int i = threadIdx.x; i < pairs * kBins; i += kHistThreads) {
         lds_hist[i] = 0ull;
         lds_h[i] = 0u;
     }
+    int hot[4];
+#pragma unroll
+    for (int fi = 0; fi < 4; ++fi)
+        hot[fi] = fi < nf ? d.hot_bin[f0 + fi] : 256;           // 256: no bin, nothing is skipped
     __syncthreads();
-    for (int r = row0 + threadIdx.x; r < row1; r += kHistThreads) {
-        const int slot = (int)d.node_of_row[r] - node0;
-        if ((unsigned)slot >= (unsigned)slots)
-            continue;
-        const int2 qh = d.qh[r];
-        for (int fi = 0; fi < nf; ++fi) {
-            const int b = d.bins[(int64_t)(f0 + fi) * d.r_pad + r];
-            const int at = (slot * fg + fi) * kBins + b;
-            atomicAdd(&lds_hist[at], (unsigned long long)(long long)qh.x);
-            atomicAdd(&lds_h[at], (unsigned int)qh.y);
+    const uint32_t *__restrict__ words = (const uint32_t *)d.bins + (int64_t)blockIdx.y * d.r_pad;
+    constexpr int kUnroll = 4;
+    for (int base = row0 + threadIdx.x; base < row1; base += kHistThreads * kUnroll) {
+        int slot[kUnroll];
+        uint32_t w[kUnroll];
+        int2 qh[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {                      // loads first
+            const int r = min(base + u * kHistThreads, row1 - 1);
+            slot[u] = (int)d.node_of_row[r] - node0;
+            w[u] = words[r];
+            qh[u] = d.qh[r];
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            if (base + u * kHistThreads >= row1 || (unsigned)slot[u] >= (unsigned)slots)
+                continue;
+#pragma unroll
+            for (int fi = 0; fi < 4; ++fi) {
+                const int b = (w[u] >> (8 * fi)) & 255;
+                if (fi >= nf || b == hot[fi])
+                    continue;                                    // rebuilt from the node's total
+                const int at = (slot[u] * 4 + fi) * kBins + b;
+                atomicAdd(&lds_hist[at], (unsigned long long)(long long)qh[u].x);
+                atomicAdd(&lds_h[at], (unsigned int)qh[u].y);
+            }
         }
     }
     __syncthreads();
     for (int i = threadIdx.x; i < pairs * kBins; i += kHistThreads) {
-        const unsigned int h = lds_h[i];
-        if (h == 0u)
-            continue;
         const int pair = i / kBins, b = i - pair * kBins;
-        const int slot = pair / fg, fi = pair - slot * fg;
+        const int slot = pair >> 2, fi = pair & 3;
         if (fi >= nf)
             continue;
         const int64_t at = (((int64_t)(pass * slots + slot) * d.n_features + (f0 + fi)) * kBins + b) * 2;
-        atomicAdd(&d.hist[at], lds_hist[i]);
-        atomicAdd(&d.hist[at + 1], (unsigned long long)h);
+        const unsigned int h = lds_h[i];
+        if (n_slabs == 1) {
+            d.hist[at] = lds_hist[i];
+            d.hist[at + 1] = (unsigned long long)h;
+        } else if (h != 0u) {
+            atomicAdd(&d.hist[at], lds_hist[i]);
+            atomicAdd(&d.hist[at + 1], (unsigned long long)h);
+        }
     }
 }
 
@@ -245,109 +301,173 @@ __device__ __forceinline__ double split_gain(long long GL, long long HL, long lo
     return (t1 + t2) - t3;
 }
 
-// Best cut of one feature for one open node: thread t owns bin t and cut t+1.
-__global__ void __launch_bounds__(kBins)
+// Best cut of one feature for one open node.  One wavefront per (node, feature); lane l owns
+// bins 4l..4l+3 and the cuts 4l+1..4l+4.  The histogram entries are cleared once read, so the
+// buffer is all zero again for the next level.
+constexpr int kSplitWaves = 4;
+
+__device__ __forceinline__ long long shfl_up_ll(long long v, int off) { return __shfl_up(v, off); }
+
+__global__ void __launch_bounds__(64 * kSplitWaves)
 train_split_kernel(const TrainDesc *__restrict__ descs, int level, Params prm)
 {
-    __shared__ long long sG[kBins], sH[kBins];
-    __shared__ double s_gain[kBins];
-    __shared__ int s_cut[kBins];
     const TrainDesc &d = descs[blockIdx.z];
-    const int f = blockIdx.x, slot = blockIdx.y, t = threadIdx.x;
-    if (f >= d.n_features)
+    const int lane = threadIdx.x & 63;
+    const int pair = blockIdx.x * kSplitWaves + (threadIdx.x >> 6);
+    const int n_slots = 1 << level;
+    if (pair >= n_slots * d.n_features)
         return;
-    const int node = (1 << level) - 1 + slot;
+    const int slot = pair / d.n_features, f = pair - slot * d.n_features;
+    const int node = n_slots - 1 + slot;
     if (d.h_state[node] != kOpen)
         return;
-    const int64_t at = (((int64_t)slot * d.n_features + f) * kBins + t) * 2;
-    sG[t] = (long long)d.hist[at];
-    sH[t] = (long long)d.hist[at + 1];
-    __syncthreads();
-    for (int off = 1; off < kBins; off <<= 1) {                  // inclusive scan over the bins
-        long long g = 0, h = 0;
-        if (t >= off) {
-            g = sG[t - off];
-            h = sH[t - off];
-        }
-        __syncthreads();
-        sG[t] += g;
-        sH[t] += h;
-        __syncthreads();
+    typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
+    u64x2 *hp = (u64x2 *)(d.hist + ((int64_t)pair * kBins + 4 * lane) * 2);
+    long long g[4], h[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const u64x2 v = hp[k];
+        g[k] = (long long)v.x;
+        h[k] = (long long)v.y;
+        hp[k] = (u64x2){0ull, 0ull};
     }
     const long long G = d.h_G[node], H = d.h_H[node];
+    // the feature's most frequent bin was not counted: it holds what the others leave
+    long long og = g[0] + g[1] + g[2] + g[3], oh = h[0] + h[1] + h[2] + h[3];
+    for (int off = 32; off > 0; off >>= 1) {
+        og += __shfl_xor(og, off);
+        oh += __shfl_xor(oh, off);
+    }
+    const int hot = d.hot_bin[f];
+    if ((hot >> 2) == lane) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if ((hot & 3) == k) {
+                g[k] = G - og;
+                h[k] = H - oh;
+            }
+    }
+    // inclusive prefix sums over the 256 bins
+#pragma unroll
+    for (int k = 1; k < 4; ++k) {
+        g[k] += g[k - 1];
+        h[k] += h[k - 1];
+    }
+    long long pg = g[3], ph = h[3];                              // this lane's total -> scan
+    for (int off = 1; off < 64; off <<= 1) {
+        const long long ug = shfl_up_ll(pg, off), uh = shfl_up_ll(ph, off);
+        if (lane >= off) {
+            pg += ug;
+            ph += uh;
+        }
+    }
+    const long long before_g = pg - g[3], before_h = ph - h[3];
     const int m = d.cut_off[f + 1] - d.cut_off[f];
-    const long long GL = sG[t], HL = sH[t];                      // left side of cut t+1
     int cut = 0;
     double gain = 0.0;
-    if (t + 1 <= m && HL >= prm.mcw && H - HL >= prm.mcw) {
-        cut = t + 1;
-        gain = split_gain(GL, HL, G, H, prm.inv_scale, prm.lambda);
-    }
-    s_gain[t] = gain;
-    s_cut[t] = cut;
-    __syncthreads();
-    for (int off = kBins / 2; off > 0; off >>= 1) {              // largest gain, lowest cut on ties
-        if (t < off) {
-            const double ga = s_gain[t], gb = s_gain[t + off];
-            const int ca = s_cut[t], cb = s_cut[t + off];
-            if (cb != 0 && (ca == 0 || gb > ga || (gb == ga && cb < ca))) {
-                s_gain[t] = gb;
-                s_cut[t] = cb;
+    long long bGL = 0, bHL = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {                                // cut 4l+k+1: left = bins 0..4l+k
+        const long long GL = before_g + g[k], HL = before_h + h[k];
+        const int j = 4 * lane + k + 1;
+        if (j <= m && HL >= prm.mcw && H - HL >= prm.mcw) {
+            const double gn = split_gain(GL, HL, G, H, prm.inv_scale, prm.lambda);
+            if (cut == 0 || gn > gain) {                         // ascending cuts: first of equals stays
+                gain = gn;
+                cut = j;
+                bGL = GL;
+                bHL = HL;
             }
         }
-        __syncthreads();
     }
-    const int best = s_cut[0];
-    const int64_t o = (int64_t)slot * d.n_features + f;
-    if (t == 0) {
-        d.best_gain[o] = s_gain[0];
-        d.best_cut[o] = best;
+    for (int off = 32; off > 0; off >>= 1) {                     // largest gain, lowest cut on ties
+        const double og2 = __shfl_xor(gain, off);
+        const int oc = __shfl_xor(cut, off);
+        const long long ogl = __shfl_xor(bGL, off), ohl = __shfl_xor(bHL, off);
+        if (oc != 0 && (cut == 0 || og2 > gain || (og2 == gain && oc < cut))) {
+            gain = og2;
+            cut = oc;
+            bGL = ogl;
+            bHL = ohl;
+        }
     }
-    if (best != 0 && t == best - 1) {
-        d.best_GL[o] = GL;
-        d.best_HL[o] = HL;
+    if (lane == 0) {
+        d.best_gain[pair] = gain;
+        d.best_cut[pair] = cut;
+        d.best_GL[pair] = bGL;
+        d.best_HL[pair] = bHL;
     }
 }
 
 // Per open node of the level: best feature, split or leaf; children get consecutive ids in
-// slot order (breadth-first numbering).  One workgroup per trainer, one thread per slot.
-__global__ void __launch_bounds__(1 << FS_TRAIN_MAX_DEPTH)
+// slot order (breadth-first numbering).  One workgroup per trainer: first every wavefront
+// finds the best feature of some of the nodes (lanes over features), then one thread per node
+// decides.
+constexpr int kPickThreads = 1024;
+constexpr int kMaxSlots = 1 << FS_TRAIN_MAX_DEPTH;
+
+__global__ void __launch_bounds__(kPickThreads)
 train_pick_kernel(const TrainDesc *__restrict__ descs, int level, Params prm)
 {
-    __shared__ int s_scan[1 << FS_TRAIN_MAX_DEPTH];
+    __shared__ int s_scan[kMaxSlots];
+    __shared__ int s_bf[kMaxSlots], s_bc[kMaxSlots];
+    __shared__ double s_bg[kMaxSlots];
     const TrainDesc &d = descs[blockIdx.x];
-    const int slot = threadIdx.x, n_slots = 1 << level;
-    const int node = n_slots - 1 + slot;
-    const bool open = slot < n_slots && d.h_state[node] == kOpen;
-    int bf = -1, bc = 0;
-    double bg = 0.0;
-    if (open && level < prm.max_depth) {
-        for (int f = 0; f < d.n_features; ++f) {
-            const int64_t o = (int64_t)slot * d.n_features + f;
-            const int c = d.best_cut[o];
-            if (c == 0)
-                continue;
-            const double g = d.best_gain[o];
-            if (bf < 0 || g > bg) {
-                bg = g;
-                bf = f;
-                bc = c;
+    const int n_slots = 1 << level;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int sl = wave; sl < n_slots; sl += kPickThreads / 64) {
+        int bf = -1, bc = 0;
+        double bg = 0.0;
+        if (level < prm.max_depth && d.h_state[n_slots - 1 + sl] == kOpen) {
+            for (int f = lane; f < d.n_features; f += 64) {      // ascending: first of equals stays
+                const int64_t o = (int64_t)sl * d.n_features + f;
+                const int c = d.best_cut[o];
+                if (c == 0)
+                    continue;
+                const double g = d.best_gain[o];
+                if (bf < 0 || g > bg) {
+                    bg = g;
+                    bf = f;
+                    bc = c;
+                }
+            }
+            for (int off = 32; off > 0; off >>= 1) {             // largest gain, lowest feature on ties
+                const double og = __shfl_xor(bg, off);
+                const int of = __shfl_xor(bf, off), oc = __shfl_xor(bc, off);
+                if (of >= 0 && (bf < 0 || og > bg || (og == bg && of < bf))) {
+                    bg = og;
+                    bf = of;
+                    bc = oc;
+                }
             }
         }
+        if (lane == 0) {
+            s_bf[sl] = bf;
+            s_bc[sl] = bc;
+            s_bg[sl] = bg;
+        }
     }
-    const bool split = open && bf >= 0 && bg > prm.min_gain;
-    s_scan[threadIdx.x] = split ? 1 : 0;
     __syncthreads();
-    for (int off = 1; off < (int)blockDim.x; off <<= 1) {
+    const int slot = threadIdx.x;
+    const int node = n_slots - 1 + slot;
+    const bool open = slot < n_slots && d.h_state[node] == kOpen;
+    const int bf = open ? s_bf[slot] : -1, bc = open ? s_bc[slot] : 0;
+    const double bg = open ? s_bg[slot] : 0.0;
+    const bool split = open && bf >= 0 && bg > prm.min_gain;
+    if (threadIdx.x < kMaxSlots)
+        s_scan[threadIdx.x] = split ? 1 : 0;
+    __syncthreads();
+    for (int off = 1; off < kMaxSlots; off <<= 1) {
         int v = 0;
-        if ((int)threadIdx.x >= off)
+        if (threadIdx.x < kMaxSlots && (int)threadIdx.x >= off)
             v = s_scan[threadIdx.x - off];
         __syncthreads();
-        s_scan[threadIdx.x] += v;
+        if (threadIdx.x < kMaxSlots)
+            s_scan[threadIdx.x] += v;
         __syncthreads();
     }
-    const int before = s_scan[threadIdx.x] - (split ? 1 : 0);
-    const int total = s_scan[blockDim.x - 1];
+    const int before = threadIdx.x < kMaxSlots ? s_scan[threadIdx.x] - (split ? 1 : 0) : 0;
+    const int total = s_scan[kMaxSlots - 1];
     const int next_id = d.counters[0];
     if (open) {
         const long long G = d.h_G[node], H = d.h_H[node];
@@ -389,7 +509,8 @@ train_part_kernel(const TrainDesc *__restrict__ descs, int level)
     const int node = d.node_of_row[r];
     if (node < (1 << level) - 1 || d.h_state[node] != kInternal)
         return;
-    const int b = d.bins[(int64_t)d.h_feat[node] * d.r_pad + r];
+    const int f = d.h_feat[node];
+    const int b = d.bins[((int64_t)(f >> 2) * d.r_pad + r) * 4 + (f & 3)];
     d.node_of_row[r] = (uint16_t)(2 * node + (b < d.h_cut[node] ? 1 : 2));
 }
 
@@ -555,14 +676,16 @@ extern "C" int fs_trainer_create(fs_trainer **out, int32_t n_features, const flo
     uint8_t *bins = nullptr;
     int32_t *d_prog_off = nullptr, *d_cut_off = nullptr;
     float *d_target = nullptr, *d_cuts = nullptr;
+    int32_t *d_hot = nullptr;
 #define TRY(x)            \
     if (rc == FS_OK)      \
     rc = (x)
-    TRY(dev_alloc(t, &bins, (size_t)h.r_pad * n_features));
+    TRY(dev_alloc(t, &bins, (size_t)h.r_pad * 4 * (size_t)((n_features + 3) / 4)));
     TRY(dev_alloc(t, &d_prog_off, (size_t)n_programs + 1));
     TRY(dev_alloc(t, &d_target, (size_t)n_programs));
     TRY(dev_alloc(t, &d_cut_off, (size_t)n_features + 1));
     TRY(dev_alloc(t, &d_cuts, (size_t)n_cuts));
+    TRY(dev_alloc(t, &d_hot, (size_t)n_features));
     TRY(dev_alloc(t, &h.row_pred, (size_t)n_rows));
     TRY(dev_alloc(t, &h.prog_pred, (size_t)n_programs));
     TRY(dev_alloc(t, &h.qh, (size_t)n_rows));
@@ -597,6 +720,7 @@ extern "C" int fs_trainer_create(fs_trainer **out, int32_t n_features, const flo
     h.target = d_target;
     h.cut_off = d_cut_off;
     h.cuts = d_cuts;
+    h.hot_bin = d_hot;
     const int32_t zeros[4] = {0, 0, 0, 0};
     e = hipMemcpyAsync(d_prog_off, prog_off, sizeof(int32_t) * ((size_t)n_programs + 1),
                        hipMemcpyDeviceToDevice, stream);
@@ -621,9 +745,14 @@ extern "C" int fs_trainer_create(fs_trainer **out, int32_t n_features, const flo
                        (const int32_t *)d_cut_off, (const float *)d_cuts, bins);
     rc = check_launch("train_bin_kernel launch");
     if (rc == FS_OK) {
+        hipLaunchKernelGGL(train_hot_bin_kernel, dim3((unsigned)n_features), dim3(256), 0, stream,
+                           (const uint8_t *)bins, (int)n_rows, h.r_pad, d_hot);
         hipLaunchKernelGGL(train_fill_kernel, dim3(1024), dim3(256), 0, stream, h.row_pred,
                            (int64_t)n_rows, bias);
-        rc = check_launch("train_fill_kernel launch");
+        // the histogram buffer starts all zero; the split kernel clears what it reads
+        hipLaunchKernelGGL(train_fill_kernel, dim3(1024), dim3(256), 0, stream, (float *)h.hist,
+                           (int64_t)hist_slots * n_features * kBins * 4, 0.0f);
+        rc = check_launch("trainer set-up kernels launch");
     }
     if (rc != FS_OK) {
         fs_trainer_destroy(t);
@@ -741,7 +870,7 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
     prm.max_depth = p->max_depth;
 
     static bool hist_configured[16] = {};
-    const size_t hist_lds = (size_t)kHistPairs * kBins * 12;
+    const size_t hist_lds = (size_t)kHistSlots * 4 * kBins * 12;
     {
         int dev = 0;
         FS_HIP(hipGetDevice(&dev));
@@ -753,28 +882,40 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
     }
     const unsigned nt = (unsigned)n_trainers;
     const unsigned row_blocks = (unsigned)((max_rows + 255) / 256);
-    const unsigned slabs = (unsigned)((max_rows + kHistRowsPerBlock - 1) / kHistRowsPerBlock);
+    // one slab per family up to kHistRowsPerSlab rows: histograms are then stored, not added
+    const int n_slabs = (max_rows + kHistRowsPerSlab - 1) / kHistRowsPerSlab;
+    const int rows_per_slab = (((max_rows + n_slabs - 1) / n_slabs) + 63) & ~63;
     for (int round = 0; round < n_rounds; ++round) {
+        prof_start(kKernTrainOther, stream);
         hipLaunchKernelGGL(train_begin_tree_kernel, dim3(nt), dim3(512), 0, stream, d);
         hipLaunchKernelGGL(train_grad_kernel, dim3((unsigned)((max_prog + 255) / 256), nt), dim3(256), 0,
                            stream, d, prm.grad_scale, 1);
+        prof_stop(stream);
         for (int level = 0; level < prm.max_depth; ++level) {
             const int n_slots = 1 << level;
-            const int fg = n_slots <= 8 ? 4 : (n_slots == 16 ? 2 : 1);
-            const int slots = n_slots < kHistPairs ? n_slots : kHistPairs;
+            const int slots = n_slots < kHistSlots ? n_slots : kHistSlots;
             const int passes = n_slots / slots;
-            hipLaunchKernelGGL(train_zero_hist_kernel, dim3(256, nt), dim3(256), 0, stream, d, n_slots);
-            hipLaunchKernelGGL(train_hist_kernel, dim3(slabs, (unsigned)((max_feat + fg - 1) / fg), nt * passes),
-                               dim3(kHistThreads), hist_lds, stream, d, level, fg, slots, passes);
-            hipLaunchKernelGGL(train_split_kernel, dim3((unsigned)max_feat, (unsigned)n_slots, nt), dim3(kBins),
-                               0, stream, d, level, prm);
-            hipLaunchKernelGGL(train_pick_kernel, dim3(nt), dim3(1 << FS_TRAIN_MAX_DEPTH), 0, stream, d, level, prm);
+            const size_t lds = (size_t)slots * 4 * kBins * 12;
+            prof_start(kKernTrainHist, stream);
+            hipLaunchKernelGGL(train_hist_kernel, dim3((unsigned)n_slabs, (unsigned)((max_feat + 3) / 4), nt * passes),
+                               dim3(kHistThreads), lds, stream, d, level, passes, rows_per_slab, n_slabs);
+            prof_stop(stream);
+            prof_start(kKernTrainSplit, stream);
+            hipLaunchKernelGGL(train_split_kernel,
+                               dim3((unsigned)((n_slots * max_feat + kSplitWaves - 1) / kSplitWaves), 1u, nt),
+                               dim3(64 * kSplitWaves), 0, stream, d, level, prm);
+            hipLaunchKernelGGL(train_pick_kernel, dim3(nt), dim3(kPickThreads), 0, stream, d, level, prm);
+            prof_stop(stream);
+            prof_start(kKernTrainOther, stream);
             hipLaunchKernelGGL(train_part_kernel, dim3(row_blocks, nt), dim3(256), 0, stream, d, level);
+            prof_stop(stream);
         }
-        hipLaunchKernelGGL(train_pick_kernel, dim3(nt), dim3(1 << FS_TRAIN_MAX_DEPTH), 0, stream, d,
+        prof_start(kKernTrainOther, stream);
+        hipLaunchKernelGGL(train_pick_kernel, dim3(nt), dim3(kPickThreads), 0, stream, d,
                            prm.max_depth, prm);
         hipLaunchKernelGGL(train_update_kernel, dim3(row_blocks, nt), dim3(256), 0, stream, d);
         hipLaunchKernelGGL(train_emit_kernel, dim3(nt), dim3(512), 0, stream, d);
+        prof_stop(stream);
         rc = check_launch("training kernels launch");
         if (rc != FS_OK)
             return rc;

@@ -429,6 +429,21 @@ def make_train_set(seed: int, n_programs: int, stmts: Tuple[int, int] = (1, 16),
     return TrainSet(X, off, y.astype(np.float32), cut_off, cuts)
 
 
+def make_train_case(seed: int = 0, scale: float = 1.0, families: int = 8,
+                    max_cuts: int = 255) -> List[TrainSet]:
+    """Training sets of one tuning job: `families` family models, each with the measured
+    programs of its member subgraphs -- 2000..6000 programs of 1..16 statements, so that the
+    job holds roughly 32 000 measured candidates (the paper's Section 5.2 quotes "more than
+    30000 candidates as training data" for a 30-subgraph network)."""
+    rng = np.random.default_rng([seed, 2002])
+    out = []
+    for i in range(families):
+        n = _scaled(int(rng.integers(2000, 6001)), scale, floor=8)
+        out.append(make_train_set(int(rng.integers(1 << 30)) + i, n, stmts=(1, 16),
+                                  max_cuts=max_cuts))
+    return out
+
+
 def make_small_family(seed: int, n_programs: int, stmts: Tuple[int, int], n_trees: int,
                       depth: int, early_leaf_q: float = 0.0, zero_frac: float = 0.3,
                       n_features: int = N_FEATURES, k: int = 16, bias: float = 0.0,
