@@ -20,6 +20,7 @@
 //   pick         once more at max_depth: what is left becomes leaves
 //   update       row output += value of the row's leaf;  emit: heap -> flat model arrays
 #include <math.h>
+#include <stdlib.h>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -31,7 +32,7 @@ namespace fs {
 
 constexpr int kHeapNodes = (1 << (FS_TRAIN_MAX_DEPTH + 1)) - 1;   // 511
 constexpr int kBins = FS_TRAIN_MAX_CUTS + 1;                      // 256
-constexpr int kHistThreads = 512;
+constexpr int kHistThreads = 1024;
 constexpr int kHistRowsPerSlab = 65536;
 
 // heap node states
@@ -205,87 +206,6 @@ train_grad_kernel(const TrainDesc *__restrict__ descs, float grad_scale, int wit
     }
 }
 
-// Histograms of one level.  A workgroup takes a slab of rows, four consecutive features (one
-// 32-bit word of bins per row) and up to kHistSlots nodes of the level, and keeps their (G, H)
-// histograms in LDS.  blockIdx = (slab, feature group, trainer * passes + pass); a pass covers
-// kHistSlots consecutive nodes.  With one slab per family the histograms are stored as they
-// are; with more they are added to the buffer (which is all zero: the split kernel clears what
-// it reads).
-constexpr int kHistSlots = 8;
-
-__global__ void __launch_bounds__(kHistThreads)
-train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, int rows_per_slab,
-                  int n_slabs)
-{
-    extern __shared__ unsigned long long lds_hist[];            // G: [pairs][256] u64, then H u32
-    const TrainDesc &d = descs[blockIdx.z / passes];
-    const int pass = blockIdx.z % passes;
-    const int row0 = blockIdx.x * rows_per_slab;
-    const int f0 = blockIdx.y * 4;
-    if (row0 >= d.n_rows || f0 >= d.n_features)
-        return;
-    const int row1 = min(row0 + rows_per_slab, d.n_rows);
-    const int nf = min(4, d.n_features - f0);
-    const int n_slots = 1 << level;
-    const int slots = min(kHistSlots, n_slots);
-    const int node0 = n_slots - 1 + pass * slots;               // heap index of slot 0
-    const int pairs = slots * 4;
-    unsigned int *lds_h = (unsigned int *)(lds_hist + pairs * kBins);
-    for (int i = threadIdx.x; i < pairs * kBins; i += kHistThreads) {
-        lds_hist[i] = 0ull;
-        lds_h[i] = 0u;
-    }
-    int hot[4];
-#pragma unroll
-    for (int fi = 0; fi < 4; ++fi)
-        hot[fi] = fi < nf ? d.hot_bin[f0 + fi] : 256;           // 256: no bin, nothing is skipped
-    __syncthreads();
-    const uint32_t *__restrict__ words = (const uint32_t *)d.bins + (int64_t)blockIdx.y * d.r_pad;
-    constexpr int kUnroll = 4;
-    for (int base = row0 + threadIdx.x; base < row1; base += kHistThreads * kUnroll) {
-        int slot[kUnroll];
-        uint32_t w[kUnroll];
-        int2 qh[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {                      // loads first
-            const int r = min(base + u * kHistThreads, row1 - 1);
-            slot[u] = (int)d.node_of_row[r] - node0;
-            w[u] = words[r];
-            qh[u] = d.qh[r];
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            if (base + u * kHistThreads >= row1 || (unsigned)slot[u] >= (unsigned)slots)
-                continue;
-#pragma unroll
-            for (int fi = 0; fi < 4; ++fi) {
-                const int b = (w[u] >> (8 * fi)) & 255;
-                if (fi >= nf || b == hot[fi])
-                    continue;                                    // rebuilt from the node's total
-                const int at = (slot[u] * 4 + fi) * kBins + b;
-                atomicAdd(&lds_hist[at], (unsigned long long)(long long)qh[u].x);
-                atomicAdd(&lds_h[at], (unsigned int)qh[u].y);
-            }
-        }
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < pairs * kBins; i += kHistThreads) {
-        const int pair = i / kBins, b = i - pair * kBins;
-        const int slot = pair >> 2, fi = pair & 3;
-        if (fi >= nf)
-            continue;
-        const int64_t at = (((int64_t)(pass * slots + slot) * d.n_features + (f0 + fi)) * kBins + b) * 2;
-        const unsigned int h = lds_h[i];
-        if (n_slabs == 1) {
-            d.hist[at] = lds_hist[i];
-            d.hist[at + 1] = (unsigned long long)h;
-        } else if (h != 0u) {
-            atomicAdd(&d.hist[at], lds_hist[i]);
-            atomicAdd(&d.hist[at + 1], (unsigned long long)h);
-        }
-    }
-}
-
 __device__ __forceinline__ double split_gain(long long GL, long long HL, long long G, long long H,
                                              double inv_scale, double lambda)
 {
@@ -301,38 +221,15 @@ __device__ __forceinline__ double split_gain(long long GL, long long HL, long lo
     return (t1 + t2) - t3;
 }
 
-// Best cut of one feature for one open node.  One wavefront per (node, feature); lane l owns
-// bins 4l..4l+3 and the cuts 4l+1..4l+4.  The histogram entries are cleared once read, so the
-// buffer is all zero again for the next level.
-constexpr int kSplitWaves = 4;
-
 __device__ __forceinline__ long long shfl_up_ll(long long v, int off) { return __shfl_up(v, off); }
 
-__global__ void __launch_bounds__(64 * kSplitWaves)
-train_split_kernel(const TrainDesc *__restrict__ descs, int level, Params prm)
+// Best cut of feature f for the open node `node`, by one wavefront: lane l holds bins 4l..4l+3
+// (g, h; the feature's most frequent bin holds 0 and is rebuilt here from the node's totals)
+// and answers for the cuts 4l+1..4l+4.  Lane 0 writes the result for `pair` = slot * F + f.
+__device__ __forceinline__ void wave_best_cut(const TrainDesc &d, const Params &prm, int node, int f,
+                                              int pair, int lane, long long (&g)[4], long long (&h)[4])
 {
-    const TrainDesc &d = descs[blockIdx.z];
-    const int lane = threadIdx.x & 63;
-    const int pair = blockIdx.x * kSplitWaves + (threadIdx.x >> 6);
-    const int n_slots = 1 << level;
-    if (pair >= n_slots * d.n_features)
-        return;
-    const int slot = pair / d.n_features, f = pair - slot * d.n_features;
-    const int node = n_slots - 1 + slot;
-    if (d.h_state[node] != kOpen)
-        return;
-    typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
-    u64x2 *hp = (u64x2 *)(d.hist + ((int64_t)pair * kBins + 4 * lane) * 2);
-    long long g[4], h[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const u64x2 v = hp[k];
-        g[k] = (long long)v.x;
-        h[k] = (long long)v.y;
-        hp[k] = (u64x2){0ull, 0ull};
-    }
     const long long G = d.h_G[node], H = d.h_H[node];
-    // the feature's most frequent bin was not counted: it holds what the others leave
     long long og = g[0] + g[1] + g[2] + g[3], oh = h[0] + h[1] + h[2] + h[3];
     for (int off = 32; off > 0; off >>= 1) {
         og += __shfl_xor(og, off);
@@ -397,6 +294,134 @@ train_split_kernel(const TrainDesc *__restrict__ descs, int level, Params prm)
         d.best_GL[pair] = bGL;
         d.best_HL[pair] = bHL;
     }
+}
+
+// Histograms of one level.  A workgroup takes a slab of rows, four consecutive features (one
+// 32-bit word of bins per row) and up to kHistSlots nodes of the level, and keeps their (G, H)
+// histograms in LDS.  blockIdx = (slab, feature group, trainer * passes + pass); a pass covers
+// kHistSlots consecutive nodes.  With one slab per family the workgroup holds the complete
+// histograms and searches the cuts itself; with more slabs the partial histograms are added
+// to the global buffer (which is all zero: the split kernel clears what it reads) and
+// train_split_kernel does the search.
+constexpr int kHistSlots = 8;
+
+__global__ void __launch_bounds__(kHistThreads)
+train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, int rows_per_slab,
+                  int n_slabs, Params prm)
+{
+    extern __shared__ unsigned long long lds_hist[];            // G: [pairs][256] u64, then H u32
+    const TrainDesc &d = descs[blockIdx.z / passes];
+    const int pass = blockIdx.z % passes;
+    const int row0 = blockIdx.x * rows_per_slab;
+    const int f0 = blockIdx.y * 4;
+    if (row0 >= d.n_rows || f0 >= d.n_features)
+        return;
+    const int row1 = min(row0 + rows_per_slab, d.n_rows);
+    const int nf = min(4, d.n_features - f0);
+    const int n_slots = 1 << level;
+    const int slots = min(kHistSlots, n_slots);
+    const int node0 = n_slots - 1 + pass * slots;               // heap index of slot 0
+    const int pairs = slots * 4;
+    unsigned int *lds_h = (unsigned int *)(lds_hist + pairs * kBins);
+    for (int i = threadIdx.x; i < pairs * kBins; i += kHistThreads) {
+        lds_hist[i] = 0ull;
+        lds_h[i] = 0u;
+    }
+    int hot[4];
+#pragma unroll
+    for (int fi = 0; fi < 4; ++fi)
+        hot[fi] = fi < nf ? d.hot_bin[f0 + fi] : 256;           // 256: no bin, nothing is skipped
+    __syncthreads();
+    const uint32_t *__restrict__ words = (const uint32_t *)d.bins + (int64_t)blockIdx.y * d.r_pad;
+    constexpr int kUnroll = 8;
+    for (int base = row0 + threadIdx.x; base < row1; base += kHistThreads * kUnroll) {
+        int slot[kUnroll];
+        uint32_t w[kUnroll];
+        int2 qh[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {                      // loads first
+            const int r = min(base + u * kHistThreads, row1 - 1);
+            slot[u] = (int)d.node_of_row[r] - node0;
+            w[u] = words[r];
+            qh[u] = d.qh[r];
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            if (base + u * kHistThreads >= row1 || (unsigned)slot[u] >= (unsigned)slots)
+                continue;
+#pragma unroll
+            for (int fi = 0; fi < 4; ++fi) {
+                const int b = (w[u] >> (8 * fi)) & 255;
+                if (fi >= nf || b == hot[fi])
+                    continue;                                    // rebuilt from the node's total
+                const int at = (slot[u] * 4 + fi) * kBins + b;
+                atomicAdd(&lds_hist[at], (unsigned long long)(long long)qh[u].x);
+                atomicAdd(&lds_h[at], (unsigned int)qh[u].y);
+            }
+        }
+    }
+    __syncthreads();
+    if (n_slabs == 1) {
+        // The whole histogram of these nodes and features is here: search the cuts right away
+        // (one wavefront per (node, feature)); nothing goes through the global buffer.
+        const int lane = threadIdx.x & 63;
+        for (int pair = threadIdx.x >> 6; pair < pairs; pair += kHistThreads / 64) {
+            const int slot = pair >> 2, fi = pair & 3;
+            const int node = node0 + slot;
+            if (fi >= nf || d.h_state[node] != kOpen)
+                continue;
+            long long g[4], h[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                g[k] = (long long)lds_hist[pair * kBins + 4 * lane + k];
+                h[k] = (long long)lds_h[pair * kBins + 4 * lane + k];
+            }
+            wave_best_cut(d, prm, node, f0 + fi, (pass * slots + slot) * d.n_features + f0 + fi, lane, g, h);
+        }
+        return;
+    }
+    for (int i = threadIdx.x; i < pairs * kBins; i += kHistThreads) {
+        const int pair = i / kBins, b = i - pair * kBins;
+        const int slot = pair >> 2, fi = pair & 3;
+        const unsigned int h = lds_h[i];
+        if (fi >= nf || h == 0u)
+            continue;
+        const int64_t at = (((int64_t)(pass * slots + slot) * d.n_features + (f0 + fi)) * kBins + b) * 2;
+        atomicAdd(&d.hist[at], lds_hist[i]);
+        atomicAdd(&d.hist[at + 1], (unsigned long long)h);
+    }
+}
+
+// Best cut of one feature for one open node.  One wavefront per (node, feature); lane l owns
+// bins 4l..4l+3 and the cuts 4l+1..4l+4.  The histogram entries are zeroed once read, so that
+// the buffer is all zero again for the next level.  Only used when a family's rows span
+// several slabs.
+constexpr int kSplitWaves = 4;
+
+__global__ void __launch_bounds__(64 * kSplitWaves)
+train_split_kernel(const TrainDesc *__restrict__ descs, int level, Params prm)
+{
+    const TrainDesc &d = descs[blockIdx.z];
+    const int lane = threadIdx.x & 63;
+    const int pair = blockIdx.x * kSplitWaves + (threadIdx.x >> 6);
+    const int n_slots = 1 << level;
+    if (pair >= n_slots * d.n_features)
+        return;
+    const int slot = pair / d.n_features, f = pair - slot * d.n_features;
+    const int node = n_slots - 1 + slot;
+    if (d.h_state[node] != kOpen)
+        return;
+    typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
+    u64x2 *hp = (u64x2 *)(d.hist + ((int64_t)pair * kBins + 4 * lane) * 2);
+    long long g[4], h[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const u64x2 v = hp[k];
+        g[k] = (long long)v.x;
+        h[k] = (long long)v.y;
+        hp[k] = (u64x2){0ull, 0ull};
+    }
+    wave_best_cut(d, prm, node, f, pair, lane, g, h);
 }
 
 // Per open node of the level: best feature, split or leaf; children get consecutive ids in
@@ -883,7 +908,13 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
     const unsigned nt = (unsigned)n_trainers;
     const unsigned row_blocks = (unsigned)((max_rows + 255) / 256);
     // one slab per family up to kHistRowsPerSlab rows: histograms are then stored, not added
-    const int n_slabs = (max_rows + kHistRowsPerSlab - 1) / kHistRowsPerSlab;
+    int slab_rows = kHistRowsPerSlab;
+    if (const char *e = getenv("FS_TUNE_TRAIN_SLAB_ROWS")) {     // tuning / test aid
+        const int v = atoi(e);
+        if (v >= 64 && v <= kHistRowsPerSlab)
+            slab_rows = v;
+    }
+    const int n_slabs = (max_rows + slab_rows - 1) / slab_rows;
     const int rows_per_slab = (((max_rows + n_slabs - 1) / n_slabs) + 63) & ~63;
     for (int round = 0; round < n_rounds; ++round) {
         prof_start(kKernTrainOther, stream);
@@ -898,12 +929,13 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
             const size_t lds = (size_t)slots * 4 * kBins * 12;
             prof_start(kKernTrainHist, stream);
             hipLaunchKernelGGL(train_hist_kernel, dim3((unsigned)n_slabs, (unsigned)((max_feat + 3) / 4), nt * passes),
-                               dim3(kHistThreads), lds, stream, d, level, passes, rows_per_slab, n_slabs);
+                               dim3(kHistThreads), lds, stream, d, level, passes, rows_per_slab, n_slabs, prm);
             prof_stop(stream);
             prof_start(kKernTrainSplit, stream);
-            hipLaunchKernelGGL(train_split_kernel,
-                               dim3((unsigned)((n_slots * max_feat + kSplitWaves - 1) / kSplitWaves), 1u, nt),
-                               dim3(64 * kSplitWaves), 0, stream, d, level, prm);
+            if (n_slabs > 1)
+                hipLaunchKernelGGL(train_split_kernel,
+                                   dim3((unsigned)((n_slots * max_feat + kSplitWaves - 1) / kSplitWaves), 1u, nt),
+                                   dim3(64 * kSplitWaves), 0, stream, d, level, prm);
             hipLaunchKernelGGL(train_pick_kernel, dim3(nt), dim3(kPickThreads), 0, stream, d, level, prm);
             prof_stop(stream);
             prof_start(kKernTrainOther, stream);

@@ -73,6 +73,18 @@ def test_regularisation_and_stopping_rules(api, T):
     check(api, T, ts, rounds=2, max_depth=3, eta=0.2, lam=1.0, grad_scale=float(1 << 10))
 
 
+def test_families_spanning_several_row_slabs(api, T, monkeypatch):
+    """Families with more rows than one histogram workgroup takes add their partial
+    histograms into the global buffer and a separate kernel searches the cuts; forced here by
+    shrinking the slab (a full slab is 65536 rows)."""
+    monkeypatch.setenv("FS_TUNE_TRAIN_SLAB_ROWS", "1000")
+    ts = W.make_train_set(27, 900, stmts=(1, 12), n_features=21, max_cuts=100)
+    assert ts.n_rows > 4000
+    check(api, T, ts, rounds=4, max_depth=6, eta=0.5, lam=1.0)
+    monkeypatch.delenv("FS_TUNE_TRAIN_SLAB_ROWS")
+    check(api, T, ts, rounds=2, max_depth=6, eta=0.5, lam=1.0)
+
+
 def test_batched_families_train_independently(api, T):
     import torch
     sets = [W.make_train_set(30 + i, n, stmts=(1, 8), n_features=nf, max_cuts=mc)
