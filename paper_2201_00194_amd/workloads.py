@@ -444,6 +444,74 @@ def make_train_case(seed: int = 0, scale: float = 1.0, families: int = 8,
     return out
 
 
+@dataclass
+class Subgraph:
+    """One subgraph of a synthetic network: measured programs to train on and a validation
+    pool with its (noise-free) true scores."""
+    family: int
+    train: TrainSet
+    val_features: np.ndarray   # float32 [R, D]
+    val_prog_off: np.ndarray   # int32 [P+1]
+    val_target: np.ndarray     # float32 [P]
+
+
+def _teacher_rows(model: Model, X: np.ndarray, depth: int) -> np.ndarray:
+    rows = np.zeros(X.shape[0], np.float64)
+    ar = np.arange(X.shape[0])
+    for t in range(model.n_trees):
+        o = int(model.tree_off[t])
+        node = np.zeros(X.shape[0], np.int64)
+        for _ in range(depth):
+            f = model.split_feature[o + node]
+            node = np.where(X[ar, f] < model.threshold[o + node], model.left[o + node],
+                            model.right[o + node])
+        rows += model.value[o + node]
+    return rows
+
+
+def make_network(seed: int = 0, n_subgraphs: int = 11, n_families: int = 4, samples: int = 256,
+                 val: int = 256, stmts: Tuple[int, int] = (1, 8), n_features: int = 32,
+                 max_cuts: int = 63, own_weight: float = 0.35, noise: float = 0.02) -> List[Subgraph]:
+    """A network in the shape of the paper's Section 3.1 study (11 subgraphs, 256 measured
+    candidates each).  Subgraphs of one family share a hidden teacher ensemble; every subgraph
+    adds a smaller teacher of its own (`own_weight`), so that pooling samples inside a family
+    helps, pooling across families hurts, and training alone starves.  All subgraphs share one
+    cut list (drawn from the union of the training features) so that any model can score any
+    subgraph's candidates."""
+    rng = np.random.default_rng([seed, 3003])
+    fam_of = np.sort(rng.integers(0, n_families, size=n_subgraphs))
+    fam_of[:n_families] = np.arange(n_families)              # every family has a member
+    fam_of = np.sort(fam_of)
+    probe = draw_features(rng, 2048, 0.3, n_features=n_features)
+    fam_teacher = [draw_model(rng, probe, 12, 4) for _ in range(n_families)]
+    parts = []
+    for s in range(n_subgraphs):
+        own = draw_model(rng, probe, 6, 3, leaf_sigma=0.1 * own_weight / 0.35)
+        def pool(n_prog):
+            off = uniform_prog_off(rng, n_prog, stmts[0], stmts[1])
+            X = draw_features(rng, int(off[-1]), 0.3, n_features=n_features)
+            rows = _teacher_rows(fam_teacher[int(fam_of[s])], X, 4) + _teacher_rows(own, X, 3)
+            y = np.add.reduceat(rows, off[:-1].astype(np.int64))
+            return X, off, y
+        Xt, offt, yt = pool(samples)
+        Xv, offv, yv = pool(val)
+        yt = yt + rng.normal(0.0, noise, size=samples)
+        parts.append((int(fam_of[s]), Xt, offt, yt.astype(np.float32), Xv, offv, yv.astype(np.float32)))
+    cut_off, cuts = draw_cuts(np.concatenate([p[1] for p in parts]), max_cuts)
+    return [Subgraph(f, TrainSet(Xt, offt, yt, cut_off, cuts), Xv, offv, yv)
+            for f, Xt, offt, yt, Xv, offv, yv in parts]
+
+
+def pool_train_sets(sets: List[TrainSet]) -> TrainSet:
+    """The measured programs of several subgraphs as one training set (same cut lists)."""
+    X = np.concatenate([t.features for t in sets])
+    lens = np.concatenate([np.diff(t.prog_off) for t in sets]).astype(np.int64)
+    off = np.zeros(lens.shape[0] + 1, np.int64)
+    np.cumsum(lens, out=off[1:])
+    return TrainSet(X, off.astype(np.int32), np.concatenate([t.target for t in sets]),
+                    sets[0].cut_off, sets[0].cuts)
+
+
 def make_small_family(seed: int, n_programs: int, stmts: Tuple[int, int], n_trees: int,
                       depth: int, early_leaf_q: float = 0.0, zero_frac: float = 0.3,
                       n_features: int = N_FEATURES, k: int = 16, bias: float = 0.0,
