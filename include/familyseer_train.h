@@ -57,6 +57,10 @@ typedef struct fs_train_params {
  * so `features` is not needed after the call's work has run; `prog_off` and `target` are
  * copied too.  Every row starts at `bias`.  max_depth / max_trees bound what fs_train_boost
  * may be asked for later (they size the buffers).  n_rows >= 1, n_programs >= 1.
+ * The content of prog_off (DEVICE) is not validated: it must start at 0, be non-decreasing
+ * and end at n_rows, as for fs_score_families; a malformed array gives undefined results.
+ * The cut lists (HOST) are validated.  The binning work is enqueued on `stream`; the small
+ * host arrays are copied with plain (synchronising) copies.
  * Errors: FS_EINVAL, FS_EUNSUPPORTED (limits), FS_ENOMEM, FS_EDEVICE.
  */
 int fs_trainer_create(fs_trainer **out, int32_t n_features, const float *features /* DEVICE */,
@@ -72,6 +76,9 @@ void fs_trainer_destroy(fs_trainer *t);
 /*
  * n_rounds boosting rounds for every trainer of the batch (families train independently; one
  * batched submission per step, no host synchronisation).  All trainers use `params`.
+ * Calls that involve the same trainer, and all training calls on one device, must be issued
+ * on one stream (or be ordered by the caller): the batch descriptors and each trainer's
+ * state are shared between calls.
  * Errors: FS_EINVAL, FS_EUNSUPPORTED (a trainer's max_depth / max_trees would be exceeded).
  */
 int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers /* HOST */, int32_t n_rounds,

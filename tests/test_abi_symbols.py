@@ -78,3 +78,39 @@ def test_host_side_validation_needs_no_gpu():
     l3b = (i32 * 3)(1, -1, -1)
     assert lib.fs_model_create(ctypes.byref(h), 4, 1, off3, sf3b, z3, l3b, r3, z3, 0.0) == -1
     assert b"feature" in lib.fs_last_error()
+
+
+def test_trainer_argument_errors_need_no_gpu():
+    """fs_trainer_create / fs_train_boost reject bad arguments before touching the device."""
+    if not os.path.exists(LIB):
+        from paper_2201_00194_amd import build
+        build.build()
+    lib = ctypes.CDLL(LIB)
+    lib.fs_last_error.restype = ctypes.c_char_p
+    i32p, f32p = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)
+    lib.fs_trainer_create.restype = ctypes.c_int
+    lib.fs_trainer_create.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32, ctypes.c_void_p,
+                                      ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32,
+                                      ctypes.c_void_p, i32p, f32p, ctypes.c_float, ctypes.c_int32,
+                                      ctypes.c_int32, ctypes.c_void_p]
+    out = ctypes.c_void_p()
+    cut_off = (ctypes.c_int32 * 3)(0, 2, 3)
+    cuts = (ctypes.c_float * 3)(0.5, 0.25, 1.0)               # feature 0: not ascending
+    fake = ctypes.c_void_p(4096)                              # never dereferenced on these paths
+
+    def create(nf=2, rows=10, progs=5, co=cut_off, cu=cuts, depth=3, trees=4, layout=1):
+        return lib.fs_trainer_create(ctypes.byref(out), nf, fake, layout, rows, fake, progs, fake,
+                                     co, cu, 0.0, depth, trees, None)
+
+    assert create() == -1 and b"ascending" in lib.fs_last_error()
+    good = (ctypes.c_float * 3)(0.25, 0.5, 1.0)
+    assert create(cu=good, nf=0) == -1
+    assert create(cu=good, rows=0) == -1
+    assert create(cu=good, depth=9) == -4                     # FS_EUNSUPPORTED
+    assert create(cu=good, trees=0) == -1
+    assert create(cu=good, layout=7) == -1
+    assert out.value is None
+    lib.fs_train_boost.restype = ctypes.c_int
+    lib.fs_train_boost.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
+                                   ctypes.c_void_p]
+    assert lib.fs_train_boost(-1, None, 1, None, None) == -1
