@@ -417,3 +417,34 @@ def test_maximum_sizes_of_the_interface(api, oracle):
                               n_features=8, k=1)
     with pytest.raises(api.FsError):
         api.fs_model.from_arrays(big.model)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_across_the_kernel_choices(api, oracle, seed):
+    """Seeded random families: feature counts on both sides of the LDS formats' limit, depths
+    0..12 perfect or irregular (so the compact, 8-byte-node, rank-coded and global-memory
+    kernels all get picked somewhere), ragged program lengths, both layouts; everything the
+    library returns is compared, three families per submission."""
+    import torch
+    rng = np.random.default_rng([seed, 31337])
+    fams = []
+    for i in range(3):
+        depth = int(rng.integers(0, 13))
+        q = float(rng.choice([0.0, 0.0, 0.15, 0.35]))
+        nf = int(rng.choice([1, 7, 64, 164, 255, 256, 300]))
+        n_trees = int(rng.integers(1, 40 if depth > 9 else 90))
+        n_prog = int(rng.integers(1, 400))
+        hi = int(rng.integers(1, 20))
+        fams.append(W.make_small_family(seed=1000 * seed + i, n_programs=n_prog, stmts=(1, hi),
+                                        n_trees=n_trees, depth=depth, early_leaf_q=q,
+                                        n_features=nf, k=int(rng.integers(1, 80)),
+                                        bias=float(rng.choice([0.0, -0.5, 0.125])),
+                                        zero_frac=float(rng.choice([0.0, 0.3, 0.9]))))
+    layouts = [int(rng.integers(0, 2)) for _ in fams]
+    devs = [api.DeviceFamily(f, layout=l, want_row_score=True, want_leaf_idx=True)
+            for f, l in zip(fams, layouts)]
+    api.fs_score_families([d.family() for d in devs])
+    api.fs_topk([d.topk_request() for d in devs])
+    torch.cuda.synchronize()
+    for f, d in zip(fams, devs):
+        check_family(oracle, f, d)

@@ -136,3 +136,17 @@ def test_errors(api):
     api.fs_train_boost([tr], 2, api.train_params(max_depth=3))              # still works
     torch.cuda.synchronize()
     assert tr.size()[0] == 2
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_training_shapes_and_parameters(api, T, seed):
+    rng = np.random.default_rng([seed, 777])
+    nf = int(rng.choice([1, 2, 3, 5, 17, 33, 64]))
+    ts = W.make_train_set(100 + seed, int(rng.integers(2, 1500)), stmts=(1, int(rng.integers(1, 30))),
+                          n_features=nf, max_cuts=int(rng.choice([1, 2, 7, 64, 255])),
+                          zero_frac=float(rng.choice([0.0, 0.3, 0.95])))
+    check(api, T, ts, rounds=int(rng.integers(1, 6)), layout=int(rng.integers(0, 2)),
+          bias=float(rng.choice([0.0, 1.5])), max_depth=int(rng.integers(0, 9)),
+          eta=float(rng.choice([0.1, 0.5, 1.0])), lam=float(rng.choice([0.0, 1.0, 7.5])),
+          min_child_weight=float(rng.choice([0.0, 1.0, 20.0])),
+          min_gain=float(rng.choice([0.0, 0.0, 0.01])))
