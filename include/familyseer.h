@@ -173,6 +173,38 @@ int fs_pack_colblock64(const float *rowmajor /* DEVICE */, int64_t n_rows, int32
 /* Number of floats an FS_COLBLOCK64 buffer needs. */
 int64_t fs_colblock64_floats(int64_t n_rows, int32_t n_features);
 
+/* ---- population compaction ------------------------------------------------------------ */
+
+/* One source of fs_gather_programs: a scored family in FS_COLBLOCK64 layout. */
+typedef struct fs_gather_src {
+    const float *features;   /* DEVICE, FS_COLBLOCK64                                      */
+    const int32_t *prog_off; /* DEVICE, n_programs+1 (content not validated, as above)     */
+    const float *score;      /* DEVICE, n_programs program scores, or NULL                 */
+    int32_t n_programs;      /* >= 0                                                       */
+} fs_gather_src;
+
+/*
+ * Carry selected programs over into a new family without leaving the device.  The search
+ * that feeds the cost model keeps the best candidates from one generation to the next
+ * (Section 2, the evolutionary search the tuner inherits; Section 3.2, pools of candidates):
+ * survivors keep their feature rows and their scores, so only new candidates need scoring.
+ * `keep` (DEVICE, n_keep <= FS_MAX_TOPK entries, e.g. the out_idx of fs_topk) indexes the
+ * concatenation of the sources' programs (source 0 first; at most 8 sources); an entry of
+ * -1 (the cut's padding) gives an empty program with score -infinity.  Output, in the order
+ * of `keep`: out_prog_off (DEVICE, n_keep+1), out_features (DEVICE, FS_COLBLOCK64, room for
+ * out_row_capacity rows rounded up to whole tiles; padding rows of the last tile are written
+ * as 0), out_score (DEVICE, n_keep, or NULL; -infinity where the source has no scores).
+ * The row count is only known on the device: it is out_prog_off[n_keep].  `status` (DEVICE,
+ * one int32) receives 0, or 1 if the rows do not fit out_row_capacity (then every offset is
+ * 0 and no row is copied), or 2 if `keep` holds an index outside the sources (such entries
+ * are treated like -1).  Output buffers must not overlap the sources.
+ * Errors (host side): FS_EINVAL, FS_EUNSUPPORTED (more than 8 sources, n_keep > FS_MAX_TOPK).
+ */
+int fs_gather_programs(int32_t n_features, int32_t n_sources, const fs_gather_src *src /* HOST */,
+                       const int32_t *keep /* DEVICE */, int32_t n_keep, float *out_features,
+                       int64_t out_row_capacity, int32_t *out_prog_off, float *out_score,
+                       int32_t *status, void *stream);
+
 /* ---- per-kernel timing (measurement aid) ----------------------------------------------------- */
 
 /* Kernel classes reported by fs_profile_end. */

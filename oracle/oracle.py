@@ -170,3 +170,29 @@ def topk(score: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
     if rc != 0:
         raise MemoryError("oracle top-k could not allocate")
     return idx, val
+
+
+def gather_programs(sources, keep):
+    """Survivors of a cut carried into a new family (the generation step of the evolutionary
+    search of Section 2): `sources` is a list of (row-major features, prog_off, scores or None);
+    `keep` indexes the concatenation of their programs, -1 meaning an empty program with score
+    -inf.  Returns (features, prog_off, scores) in the order of `keep`.  Plain Python loops."""
+    first = [0]
+    for _, off, _ in sources:
+        first.append(first[-1] + len(off) - 1)
+    nf = sources[0][0].shape[1]
+    rows, out_off, out_sc = [], [0], []
+    for p in keep:
+        p = int(p)
+        if p < 0:
+            out_off.append(out_off[-1])
+            out_sc.append(-np.inf)
+            continue
+        s = max(i for i in range(len(sources)) if first[i] <= p)
+        X, off, sc = sources[s]
+        q = p - first[s]
+        rows.append(X[off[q]:off[q + 1]])
+        out_off.append(out_off[-1] + int(off[q + 1] - off[q]))
+        out_sc.append(float(sc[q]) if sc is not None else -np.inf)
+    feats = np.concatenate(rows) if rows else np.zeros((0, nf), np.float32)
+    return feats.astype(np.float32), np.asarray(out_off, np.int32), np.asarray(out_sc, np.float32)

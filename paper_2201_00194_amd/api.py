@@ -397,3 +397,36 @@ def fs_train_boost(trainers, n_rounds: int, params: _FsTrainParams,
                    stream: Optional[torch.cuda.Stream] = None) -> None:
     arr = (ctypes.c_void_p * max(1, len(trainers)))(*[t.handle for t in trainers])
     _check(_lib.fs_train_boost(len(trainers), arr, n_rounds, ctypes.byref(params), _stream_ptr(stream)))
+
+
+# ---- population compaction ----------------------------------------------------------------------
+
+class _FsGatherSrc(ctypes.Structure):
+    _fields_ = [("features", ctypes.c_void_p), ("prog_off", ctypes.c_void_p),
+                ("score", ctypes.c_void_p), ("n_programs", ctypes.c_int32)]
+
+
+_lib.fs_gather_programs.restype = ctypes.c_int
+_lib.fs_gather_programs.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(_FsGatherSrc),
+                                    ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
+                                    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+
+
+def fs_gather_programs(n_features: int, sources, keep: torch.Tensor, n_keep: int,
+                       out_features: torch.Tensor, out_row_capacity: int,
+                       out_prog_off: torch.Tensor, out_score: Optional[torch.Tensor],
+                       status: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """`sources`: sequence of (features, prog_off, score-or-None, n_programs) device tensors."""
+    arr = (_FsGatherSrc * max(1, len(sources)))()
+    for i, (x, off, sc, n) in enumerate(sources):
+        arr[i] = _FsGatherSrc(_ptr(x), _ptr(off), _ptr(sc), n)
+    _check(_lib.fs_gather_programs(n_features, len(sources), arr, _ptr(keep), n_keep,
+                                   _ptr(out_features), out_row_capacity, _ptr(out_prog_off),
+                                   _ptr(out_score), _ptr(status), _stream_ptr(stream)))
+
+
+def unpack_colblock64(x: torch.Tensor, n_rows: int, n_features: int) -> np.ndarray:
+    """Host copy of an FS_COLBLOCK64 buffer as a row-major [n_rows, n_features] array (tests)."""
+    tiles = (n_rows + 63) // 64
+    a = x[: tiles * n_features * 64].cpu().numpy().reshape(tiles, n_features, 64)
+    return np.ascontiguousarray(a.transpose(0, 2, 1).reshape(tiles * 64, n_features)[:n_rows])

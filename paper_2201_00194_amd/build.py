@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfamilyseer.so")
 
-SOURCES = ["fs_api.hip", "fs_model.hip", "fs_traverse_lds.hip", "fs_rank.hip", "fs_traverse_global.hip", "fs_segsum.hip", "fs_topk.hip", "fs_pack.hip", "fs_train.hip"]
+SOURCES = ["fs_api.hip", "fs_model.hip", "fs_traverse_lds.hip", "fs_rank.hip", "fs_traverse_global.hip", "fs_segsum.hip", "fs_topk.hip", "fs_pack.hip", "fs_train.hip", "fs_gather.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

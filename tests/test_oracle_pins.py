@@ -356,3 +356,23 @@ def test_entry_points_agree_and_threads_do_not_change_bits(oracle):
                 n = m.left[o + n] if go_left else m.right[o + n]
             acc = np.float32(acc + m.value[o + n])
         assert rs[r] == acc
+
+
+def test_gather_programs_is_plain_indexing(oracle):
+    """With one row per program the gather is numpy's fancy indexing; with longer programs it
+    is the concatenation of the selected row slices; -1 stands for an empty program."""
+    rng = np.random.default_rng(9)
+    X = rng.standard_normal((40, 6)).astype(np.float32)
+    sc = rng.standard_normal(40).astype(np.float32)
+    keep = rng.integers(0, 40, 25)
+    f, off, s = oracle.gather_programs([(X, np.arange(41, dtype=np.int32), sc)], keep)
+    assert np.array_equal(f, X[keep]) and np.array_equal(off, np.arange(26)) and np.array_equal(s, sc[keep])
+    # two sources, ragged programs, by hand
+    A = np.arange(12, dtype=np.float32).reshape(6, 2)
+    B = 100 + np.arange(8, dtype=np.float32).reshape(4, 2)
+    offA, offB = np.array([0, 1, 4, 6], np.int32), np.array([0, 0, 4], np.int32)
+    f, off, s = oracle.gather_programs([(A, offA, np.array([1., 2., 3.], np.float32)), (B, offB, None)],
+                                       [4, -1, 1, 3, 0])
+    assert off.tolist() == [0, 4, 4, 7, 7, 8]
+    assert np.array_equal(f, np.concatenate([B[0:4], A[1:4], A[0:1]]))
+    assert s[2] == 2.0 and s[4] == 1.0 and np.isneginf(s[0]) and np.isneginf(s[1]) and np.isneginf(s[3])
