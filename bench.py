@@ -44,6 +44,10 @@ def parse():
                          "measured programs (train_cost_model of Algorithm 1); a step is one round "
                          "for all families")
     ap.add_argument("--depth", type=int, default=6, help="--train: tree depth")
+    ap.add_argument("--evolve", action="store_true",
+                    help="instead of scoring a fixed pool: generations of a search with a resident "
+                         "population (score only the new candidates, cut, carry the survivors over "
+                         "on the device); a step is one generation")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debug only)")
     ap.add_argument("--trees", type=int, default=None, help="override trees per family (debug only)")
@@ -182,6 +186,84 @@ def train_main(args, np, torch, api, W):
     print(json.dumps(out))
 
 
+def evolve_main(args, np, torch, api, W):
+    """Generations of one family's search: population of 16384 programs resident on the device,
+    49152 new candidates per generation (8 statements each), irregular 200-tree model as in the
+    power-law workload.  Per generation: fs_score_families on the new candidates only, fs_topk
+    over old + new scores, fs_gather_programs into the next population buffer."""
+    n_pop, n_new, stmts, nf = 16384, int(49152 * args.scale), 8, 164
+    t0 = time.time()
+    rng = np.random.default_rng([args.seed, 5005])
+    probe = W.draw_features(rng, 4096, 0.5)
+    model = W.draw_model(rng, probe, args.trees or 200, 8, early_leaf_q=0.2)
+    pool = W.Family(model, W.draw_features(rng, (n_pop + n_new) * stmts, 0.5),
+                    W.fixed_prog_off(n_pop + n_new, stmts), n_pop)
+    gen_s = time.time() - t0
+    handle = api.fs_model.from_arrays(model)
+    first = W.Family(model, pool.features[: n_pop * stmts], W.fixed_prog_off(n_pop, stmts), n_pop)
+    new = W.Family(model, pool.features[n_pop * stmts:], W.fixed_prog_off(n_new, stmts), n_pop)
+    d_first = api.DeviceFamily(first, model=handle)
+    d_new = api.DeviceFamily(new, model=handle)            # the same candidates every generation
+    cap = n_pop * stmts
+    pops = [dict(x=torch.zeros(((cap + 63) // 64) * nf * 64, dtype=torch.float32, device="cuda"),
+                 off=torch.zeros(n_pop + 1, dtype=torch.int32, device="cuda"),
+                 sc=torch.zeros(n_pop + n_new, dtype=torch.float32, device="cuda")) for _ in range(2)]
+    pops[0]["x"].copy_(d_first.features[: pops[0]["x"].numel()])
+    pops[0]["off"].copy_(d_first.prog_off)
+    keep = torch.zeros(n_pop, dtype=torch.int32, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    api.fs_score_families([api.Family(handle, pops[0]["x"], api.FS_COLBLOCK64, cap, pops[0]["off"],
+                                      pops[0]["sc"][:n_pop], None, None)])
+    state = {"cur": 0}
+
+    def step():
+        c = pops[state["cur"]]
+        n = pops[1 - state["cur"]]
+        api.fs_score_families([api.Family(handle, d_new.features, api.FS_COLBLOCK64, new.n_rows,
+                                          d_new.prog_off, c["sc"][n_pop:], None, None)])
+        api.fs_topk([api.TopkRequest(c["sc"], n_pop + n_new, n_pop, keep, None)])
+        api.fs_gather_programs(nf, [(c["x"], c["off"], c["sc"][:n_pop], n_pop),
+                                    (d_new.features, d_new.prog_off, c["sc"][n_pop:], n_new)],
+                               keep, n_pop, n["x"], cap, n["off"], n["sc"][:n_pop], status)
+        state["cur"] = 1 - state["cur"]
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    api.fs_profile_begin(8 * args.steps + 8)
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    prof = api.fs_profile_end()
+    assert int(status.item()) == 0
+    ms = e0.elapsed_time(e1) / args.steps
+    trav_ms, trav_n = prof["traverse"]
+    alg_bytes = new.n_rows * (nf * 4 + 4) + 8 * model.n_nodes
+    trav_avg = trav_ms / max(1, trav_n)
+    achieved = alg_bytes / (trav_avg * 1e-3) / 1e9 if trav_avg > 0 else 0.0
+    out = {"metric": "candidate statement-rows per second through one search generation "
+                     "(score new, cut, carry survivors over)",
+           "value": round(new.n_rows / (ms * 1e-3), 1), "unit": "rows/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+           "data": "synthetic",
+           "config": {"workload": "evolutionary generation: population %d, %d new candidates x %d "
+                                  "statements, %d trees" % (n_pop, n_new, stmts, model.n_trees),
+                      "seed": args.seed, "scale": args.scale},
+           "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                        "kernel": "traverse_lds_kernel", "kernel_avg_ms": round(trav_avg, 5),
+                        "algorithmic_bytes_per_launch": int(alg_bytes)},
+           "kernels_ms_per_step": {k: round(v[0] / max(1, args.steps), 5) for k, v in prof.items()
+                                   if v[1]},
+           "workload_gen_s": round(gen_s, 2)}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -198,6 +280,8 @@ def main():
     torch.cuda.set_device(0)
     if args.train:
         return train_main(args, np, torch, api, W)
+    if args.evolve:
+        return evolve_main(args, np, torch, api, W)
 
     t0 = time.time()
     if args.foresee:

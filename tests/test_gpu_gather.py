@@ -89,3 +89,62 @@ def test_gather_capacity_bad_indices_and_empty_requests(api, oracle):
     assert status == 0 and off.tolist() == [0]
     with pytest.raises(api.FsError):
         gather(api, devs, np.zeros(api.FS_MAX_TOPK + 1, np.int32), capacity=64)
+
+
+def test_generations_with_a_resident_population_match_rescoring_everything(api, oracle):
+    """Three generations of: score only the new candidates, cut (old scores + new scores) to the
+    population size, gather the survivors from (population, new) into the next population --
+    no host round trip in between.  The oracle scores everything from scratch every generation;
+    programs, order and scores of the final population must be identical."""
+    import torch
+    n_pop, nf = 96, 164
+    base = W.make_small_family(seed=81, n_programs=n_pop, stmts=(1, 7), n_trees=30, depth=6,
+                               early_leaf_q=0.2, k=n_pop)
+    news = [W.make_small_family(seed=82 + g, n_programs=150, stmts=(1, 7), n_trees=1, depth=1, k=1)
+            for g in range(3)]
+    model = base.model
+    handle = api.fs_model.from_arrays(model)
+    cap_rows = 7 * n_pop
+    # device: two population buffers, one score buffer [n_pop + n_new]
+    pops = []
+    for _ in range(2):
+        pops.append(dict(x=torch.zeros(((cap_rows + 63) // 64) * nf * 64, dtype=torch.float32, device="cuda"),
+                         off=torch.zeros(n_pop + 1, dtype=torch.int32, device="cuda")))
+    sbuf = [torch.zeros(n_pop + 150, dtype=torch.float32, device="cuda") for _ in range(2)]
+    scores = sbuf[0]
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    keep = torch.zeros(n_pop, dtype=torch.int32, device="cuda")
+    d0 = api.DeviceFamily(base, model=handle)
+    pops[0]["x"][: d0.features.numel()] = d0.features
+    pops[0]["off"].copy_(d0.prog_off)
+    api.fs_score_families([api.Family(handle, pops[0]["x"], api.FS_COLBLOCK64, base.n_rows,
+                                      pops[0]["off"], scores[:n_pop], None, None)])
+    # host twin
+    hX, hoff = base.features, base.prog_off
+    hs = oracle.program_scores(oracle.row_scores(model, hX), hoff)
+    cur = 0
+    for g, nw in enumerate(news):
+        dn = api.DeviceFamily(nw, model=handle)
+        api.fs_score_families([api.Family(handle, dn.features, api.FS_COLBLOCK64, nw.n_rows, dn.prog_off,
+                                          scores[n_pop:], None, None)])
+        api.fs_topk([api.TopkRequest(scores, n_pop + 150, n_pop, keep, None)])
+        nxt = 1 - cur
+        api.fs_gather_programs(nf, [(pops[cur]["x"], pops[cur]["off"], scores[:n_pop], n_pop),
+                                    (dn.features, dn.prog_off, scores[n_pop:], 150)],
+                               keep, n_pop, pops[nxt]["x"], cap_rows, pops[nxt]["off"],
+                               sbuf[nxt][:n_pop], status)          # outputs never overlap sources
+        cur = nxt
+        scores = sbuf[cur]
+        # oracle: everything again
+        ns = oracle.program_scores(oracle.row_scores(model, nw.features), nw.prog_off)
+        idx, _ = oracle.topk(np.concatenate([hs, ns]), n_pop)
+        hX, hoff, hs = oracle.gather_programs([(hX, hoff, hs), (nw.features, nw.prog_off, ns)], idx)
+        again = oracle.program_scores(oracle.row_scores(model, hX), hoff)
+        assert np.array_equal(again.view(np.uint32), hs.view(np.uint32))
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    off = pops[cur]["off"].cpu().numpy()
+    assert np.array_equal(off, hoff)
+    assert np.array_equal(scores[:n_pop].cpu().numpy().view(np.uint32), hs.view(np.uint32))
+    got = api.unpack_colblock64(pops[cur]["x"], int(hoff[-1]), nf)
+    assert np.array_equal(got.view(np.uint32), hX.view(np.uint32))
