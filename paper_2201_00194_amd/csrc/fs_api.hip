@@ -203,6 +203,16 @@ extern "C" int64_t fs_colblock64_floats(int64_t n_rows, int32_t n_features)
 }
 
 // ---- scoring -----------------------------------------------------------------------------------
+// Row-major tiles can be transposed on their way into LDS (through the still unused chunk
+// region) when the model takes an LDS kernel, rows are whole 16-byte pieces and at least 8
+// padded rows fit below the tiles.  Other row-major families are re-tiled into scratch first
+// (the rank-coding kernel reads column-blocked tiles).
+static bool rowmajor_in_kernel(const fs_model *m)
+{
+    return m->lds_ok && !m->rank_ok && m->n_features % 4 == 0 &&
+           m->lds_tile0 >= 8 * (m->n_features + 1) * 4;
+}
+
 extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void *stream_)
 {
     hipStream_t stream = (hipStream_t)stream_;
@@ -250,7 +260,8 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
             scratch_floats += (size_t)a.n_rows;
         if (a.model->rank_ok)                                // u16 rank tiles, in float units
             scratch_floats += (size_t)((a.n_rows + 63) / 64) * 32 * (size_t)a.model->n_features + 4;
-        if ((a.model->rank_ok || a.model->lds_ok) && a.layout == FS_ROWMAJOR)   // re-tiled copy
+        if ((a.model->rank_ok || a.model->lds_ok) && a.layout == FS_ROWMAJOR &&
+            !rowmajor_in_kernel(a.model))                                         // re-tiled copy
             scratch_floats += (size_t)((a.n_rows + 63) / 64) * 64 * (size_t)a.model->n_features + 4;
     }
     rc = ensure_scratch(ctx, scratch_floats);
@@ -299,13 +310,15 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         d.lds_tile0 = a.model->lds_tile0;
         d.lds_tiles = a.model->lds_tiles;
         d.compact = a.model->compact ? 1 : 0;
-        // Row-major features of a model that has an LDS format are re-tiled into scratch first
-        // (one extra pass over the features); from then on the family is column-blocked.
+        // Row-major features of a model that has an LDS format: transposed inside the LDS kernel
+        // where that is possible, else re-tiled into scratch first (one extra pass over the
+        // features; from then on the family is column-blocked).
         d.rowmajor_src = nullptr;
         d.retile_block0 = (int32_t)retile_blocks;
         d.retile_colblocks = 0;
         const bool fast = a.model->rank_ok || a.model->lds_ok;
-        if (fast && a.layout == FS_ROWMAJOR && a.n_rows > 0) {
+        const bool in_kernel = a.layout == FS_ROWMAJOR && rowmajor_in_kernel(a.model);
+        if (fast && a.layout == FS_ROWMAJOR && a.n_rows > 0 && !in_kernel) {
             const int64_t tiles = (a.n_rows + 63) / 64;
             scratch_pos = (scratch_pos + 3) & ~(size_t)3;
             d.rowmajor_src = a.features;
@@ -354,7 +367,7 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
             rk_blocks += (tiles + a.model->rk_tiles - 1) / a.model->rk_tiles;
             if (a.leaf_idx && a.n_rows > 0)
                 rk_dump = true;
-        } else if (a.model->lds_ok && colblock) {
+        } else if (a.model->lds_ok && (colblock || in_kernel)) {
             const int64_t tiles = (a.n_rows + 63) / 64;
             const int md = a.model->lds_mode;
             lds_blocks[md] += (tiles + a.model->lds_tiles - 1) / a.model->lds_tiles;

@@ -157,8 +157,58 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
         for (int j = 0; j < kPrefetchRegs; ++j)
             pf[j] = src[min(tid + j * kLdsThreads, n16 - 1)];
     }
-    // ---- feature tiles: consecutive tiles are one contiguous run in HBM ----
-    {
+    // ---- feature tiles ----
+    if (d.layout == FS_ROWMAJOR) {
+        // Row-major input (the host side only sends it here when F % 4 == 0 and at least 8
+        // padded rows fit below tile0): a tile is 64 consecutive rows = one contiguous run.  It
+        // is fetched with 16-byte loads into a staging area at LDS offset 0 (the chunk region,
+        // not yet in use) with a row stride of F + 1 words, as many rows at a time as fit, then
+        // copied across with lane = row: the odd stride makes the column reads conflict-free,
+        // the writes are whole columns.
+        const uint32_t Fp = (uint32_t)F + 1u;
+        const int stage_rows = min(64, (int)(tile0 / (4u * Fp)));   // rows the staging area takes
+        for (int t = 0; t < tiles_here; ++t) {
+            const int r0 = (tile_first + t) * 64;
+            const int rows_here = min(64, d.n_rows - r0);
+            for (int s0 = 0; s0 < 64; s0 += stage_rows) {            // uniform trip count
+                const int s1 = min(s0 + stage_rows, rows_here);      // rows [s0, s1) of the tile
+                if (s0 < s1) {
+                    auto src = FS_GLOBAL(const u32x4, d.features + (int64_t)(r0 + s0) * F);
+                    const int n16 = (s1 - s0) * (F >> 2);
+                    for (int base = tid; base < n16; base += kTileBatch * kLdsThreads) {
+                        u32x4 t4[kTileBatch];
+#pragma unroll
+                        for (int q = 0; q < kTileBatch; ++q)
+                            t4[q] = src[min(base + q * kLdsThreads, n16 - 1)];
+#pragma unroll
+                        for (int q = 0; q < kTileBatch; ++q) {
+                            const int i = base + q * kLdsThreads;
+                            if (i < n16) {
+                                const int e = 4 * i, row = e / F, col = e - row * F;
+                                const uint32_t at = 4u * ((uint32_t)row * Fp + (uint32_t)col);
+                                lds_store_f(at, __uint_as_float(t4[q].x));
+                                lds_store_f(at + 4u, __uint_as_float(t4[q].y));
+                                lds_store_f(at + 8u, __uint_as_float(t4[q].z));
+                                lds_store_f(at + 12u, __uint_as_float(t4[q].w));
+                            }
+                        }
+                    }
+                }
+                __syncthreads();
+                if (lane >= s0 && lane < s0 + stage_rows) {
+                    for (int j = wave; j < F; j += kLdsWaves) {
+                        const float v = lane < s1 ? lds_f(4u * ((uint32_t)(lane - s0) * Fp + (uint32_t)j)) : 0.0f;
+                        lds_store_f(tile0 + (uint32_t)t * tile_bytes + (uint32_t)j * 256u + 4u * (uint32_t)lane, v);
+                    }
+                }
+                __syncthreads();   // the staging area is free again (next rows, then the chunk)
+            }
+        }
+        if (tid < 64 * tiles_here)
+            lds_store_f(tile0 + (uint32_t)(tid >> 6) * tile_bytes + (uint32_t)F * 256u +
+                            4u * (uint32_t)(tid & 63), __builtin_nanf(""));
+    } else {
+        // consecutive tiles are one contiguous run in HBM
         auto src = FS_GLOBAL(const u32x4, d.features + (int64_t)tile_first * F * 64);
         const int per_tile = F * 16;                       // 16-byte pieces per tile
         const int n16 = tiles_here * per_tile;

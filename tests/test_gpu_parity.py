@@ -349,6 +349,35 @@ def test_rowmajor_input_is_retiled_into_the_fast_kernels(api, oracle):
     assert prof["traverse"][1] == 1 and prof["traverse_rank"][1] == 1
 
 
+def test_rowmajor_input_transposed_inside_the_lds_kernel(api, oracle):
+    """Row-major families whose model takes an LDS kernel and whose feature count is a multiple
+    of four are read as they are (no re-tiling pass): ragged last tile, a one-row family, special
+    values, 164 and 64 features (two and three tiles per workgroup).  A 30-feature family in the
+    same call still goes through the re-tiling pass."""
+    import torch
+    fams = [W.make_small_family(seed=91, n_programs=333, stmts=(1, 9), n_trees=60, depth=7,
+                                early_leaf_q=0.2, k=16),
+            W.make_small_family(seed=92, n_programs=1, stmts=(1, 1), n_trees=5, depth=3, k=1),
+            W.make_small_family(seed=93, n_programs=200, stmts=(2, 5), n_trees=40, depth=6,
+                                n_features=64, k=9, bias=0.5),
+            W.make_small_family(seed=94, n_programs=90, stmts=(1, 4), n_trees=25, depth=5,
+                                n_features=30, k=5)]
+    x = fams[0].features
+    x[3, 7], x[64, 0], x[65, 163], x[130, 5] = np.nan, np.inf, -np.inf, -0.0
+    api.fs_profile_begin(32)
+    devs = run_families(api, fams[:3], api.FS_ROWMAJOR)
+    prof = api.fs_profile_end()
+    for f, d in zip(fams[:3], devs):
+        check_family(oracle, f, d)
+    assert prof["pack"][1] == 0 and prof["traverse"][1] == 1 and prof["traverse_global"][1] == 0
+    api.fs_profile_begin(32)
+    devs = run_families(api, fams, api.FS_ROWMAJOR)
+    prof = api.fs_profile_end()
+    for f, d in zip(fams, devs):
+        check_family(oracle, f, d)
+    assert prof["pack"][1] == 1
+
+
 def test_foresee_step_shape_many_small_pools_sharing_a_family_model(api, oracle):
     """The family-scoped step of the paper's Algorithm 1: the family's one model estimates the
     candidates of several member subgraphs, and g*p = 16 candidates per subgraph go on
