@@ -54,11 +54,11 @@ enum {
 
 /* Feature matrix layouts. */
 enum {
-    FS_ROWMAJOR = 0,   /* x[r][j] at r*n_features + j.  Accepted everywhere.  Where the model's
-                          kernel allows it (n_features a multiple of 4, no rank coding) the
-                          tiles are transposed on their way into LDS (about 10 % slower than
-                          FS_COLBLOCK64); otherwise the library re-tiles the matrix into its
-                          scratch first (one extra pass over the features)                  */
+    FS_ROWMAJOR = 0,   /* x[r][j] at r*n_features + j.  Accepted everywhere.  The kernels that
+                          first touch the features read it themselves where they can (rank-coded
+                          models always; other LDS-staged models when n_features is a multiple
+                          of 4): 10-20 % slower than FS_COLBLOCK64.  Otherwise the library
+                          re-tiles the matrix into its scratch first (one extra pass)           */
     FS_COLBLOCK64 = 1  /* tiles of 64 rows, feature-major inside a tile:
                           x[r][j] at (r/64)*n_features*64 + j*64 + (r%64);
                           the last tile is padded to 64 rows (padding content is ignored);

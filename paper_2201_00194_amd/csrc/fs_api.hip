@@ -203,14 +203,15 @@ extern "C" int64_t fs_colblock64_floats(int64_t n_rows, int32_t n_features)
 }
 
 // ---- scoring -----------------------------------------------------------------------------------
-// Row-major tiles can be transposed on their way into LDS (through the still unused chunk
-// region) when the model takes an LDS kernel, rows are whole 16-byte pieces and at least 8
-// padded rows fit below the tiles.  Other row-major families are re-tiled into scratch first
-// (the rank-coding kernel reads column-blocked tiles).
+// Row-major input needs no pass of its own where the first kernel to touch the features can
+// read it: the rank-coding kernel always can; the LDS kernel transposes tiles on their way
+// into LDS (through the still unused chunk region) when rows are whole 16-byte pieces and at
+// least 8 padded rows fit below the tiles.  Other row-major families are re-tiled into scratch.
 static bool rowmajor_in_kernel(const fs_model *m)
 {
-    return m->lds_ok && !m->rank_ok && m->n_features % 4 == 0 &&
-           m->lds_tile0 >= 8 * (m->n_features + 1) * 4;
+    if (m->rank_ok)
+        return true;
+    return m->lds_ok && m->n_features % 4 == 0 && m->lds_tile0 >= 8 * (m->n_features + 1) * 4;
 }
 
 extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void *stream_)
@@ -348,7 +349,7 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         // Column-blocked features: deep perfect-tree models are rank-coded first and walked by
         // the rank kernel, other models that fit the LDS format take the LDS kernel; everything
         // else is walked from global memory.
-        if (a.model->rank_ok && colblock) {
+        if (a.model->rank_ok && (colblock || in_kernel)) {
             const int64_t tiles = (a.n_rows + 63) / 64;
             scratch_pos = (scratch_pos + 3) & ~(size_t)3;            // 16-byte aligned tiles
             d.ranks = (uint16_t *)(ctx->scratch + scratch_pos);

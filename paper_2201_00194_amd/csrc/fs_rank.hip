@@ -89,13 +89,20 @@ rank_code_kernel(const FamDesc *__restrict__ descs, int n_families)
     // while the current round is searched.
     const int n_waves = kBinThreads / 64;
     const int rounds_per_tile = (gf + kBinChains - 1) / kBinChains;
+    // Element (tile, feature f0 + j, lane) of the input: column-blocked tiles, or row-major rows
+    // (the row index is clamped: the last tile of a row-major matrix has no padding rows).
+    const bool rowmajor = d.layout == FS_ROWMAJOR;
+    auto x_at = [&](int tile, int j) -> int64_t {
+        if (rowmajor)
+            return (int64_t)min(tile * 64 + lane, d.n_rows - 1) * F + f0 + j;
+        return ((int64_t)tile * F + f0 + j) * 64 + lane;
+    };
     int t = wave, jg = 0;                            // current round: tile t, features 4*jg..
     float xn[kBinChains];
     if (t < nt) {
-        const int64_t base = ((int64_t)(t0 + t) * F + f0) * 64 + lane;
 #pragma unroll
         for (int k = 0; k < kBinChains; ++k)
-            xn[k] = X[base + (int64_t)min(k, gf - 1) * 64];
+            xn[k] = X[x_at(t0 + t, min(k, gf - 1))];
     }
     while (t < nt) {
         const int j0 = jg * kBinChains;
@@ -115,10 +122,9 @@ rank_code_kernel(const FamDesc *__restrict__ descs, int n_families)
             tn = t + n_waves;
         }
         if (tn < nt) {
-            const int64_t nb = ((int64_t)(t0 + tn) * F + f0) * 64 + lane;
 #pragma unroll
             for (int k = 0; k < kBinChains; ++k)
-                xn[k] = X[nb + (int64_t)min(jn * kBinChains + k, gf - 1) * 64];
+                xn[k] = X[x_at(t0 + tn, min(jn * kBinChains + k, gf - 1))];
         }
         for (int s = 0; s < q; ++s) {
             float c[kBinChains];
