@@ -5,10 +5,10 @@
 // result is reproducible bit for bit.  One lane owns one program.  A wavefront streams
 // the contiguous row range of its 64 programs through registers 64 rows at a time
 // (coalesced loads) and every lane pulls the rows it owns out of the current window with
-// wavefront shuffles, one row per step, in order.  That suits short programs (many programs
-// per 64-row window).  When the wavefront's programs average more than 16 rows, few lanes
-// would be busy per window; then every lane reads its own rows straight from memory, four
-// loads in flight, still adding them in ascending order.
+// wavefront shuffles, one row per step, in order.  That suits very short programs (many
+// programs per 64-row window).  When the wavefront's programs average more than 4 rows (measured:
+// from 8 rows per program on the shuffles lose), every lane reads its own rows straight from
+// memory instead, four loads in flight, still adding them in ascending order.
 #include "fs_internal.h"
 
 namespace fs {
@@ -46,7 +46,7 @@ segsum_kernel(const FamDesc *__restrict__ descs, int n_families)
 
     float acc = 0.0f;
     int cur = begin;
-    if (w_end - w_begin > 16 * (p_last - p_wave)) {        // long programs: per-lane reads
+    if (w_end - w_begin > 4 * (p_last - p_wave)) {         // longer programs: per-lane reads
         while (__any(cur < end)) {
             float v[4];
 #pragma unroll
