@@ -316,16 +316,20 @@ def main():
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     w0 = time.perf_counter()
     e0.record()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - w0) * 1e3
     prof = api.fs_profile_end()
     ev_ms = e0.elapsed_time(e1)
     ms_per_step = max(ev_ms, 0.0) / args.steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     rows_per_s = n_rows / (ms_per_step * 1e-3)
 
     # ---- roofline of the dominant kernel (LDS-staged traversal) --------------------------------
@@ -370,6 +374,8 @@ def main():
         "kernels_ms_per_step": {k: round(v[0] / max(1, args.steps), 5) for k, v in prof.items()},
         "topk_us_per_family": round(prof["topk"][0] / max(1, prof["topk"][1]) * 1e3
                                     / max(1, len(case.families)), 3),
+        "ms_per_step_median": round(per_step[len(per_step) // 2], 5),
+        "ms_per_step_min": round(per_step[0], 5),
         "host_wall_ms_per_step": round(wall_ms / args.steps, 5),
         "workload_gen_s": round(gen_s, 2),
     }
@@ -417,9 +423,17 @@ def main():
                 desc.append("family %d programs [0,%d) = %d rows" % (fi, p_end, rows))
         if whole:
             desc.insert(0, "%d whole families" % whole)
+        # the same oracle on one thread, on the first 1/16 of the first sampled family
+        f0 = next(f for f in case.families if f.n_rows > 0 and f.n_programs > 0)
+        p1 = max(1, min(f0.n_programs, int(2.0e10 / 16 / max(1.0, f0.model.n_trees * max(1.0, mean_path)
+                                                                 * max(1.0, f0.n_rows / f0.n_programs)))))
+        c0 = time.perf_counter()
+        O.score_programs(f0.model, f0.features[: int(f0.prog_off[p1])], f0.prog_off[: p1 + 1], threads=1)
+        t1 = time.perf_counter() - c0
         out["cpu_baseline"] = {
             "value": round(sample_rows / t_cpu, 1) if t_cpu > 0 else None, "unit": "rows/s",
             "cores": threads, "kind": "oracle",
+            "value_1_thread": round(int(f0.prog_off[p1]) / t1, 1) if t1 > 0 else None,
             "sample": "; ".join(desc) + " (%d rows); scored + cut in %.2f s wall" % (sample_rows, t_cpu)}
     print(json.dumps(out))
 
