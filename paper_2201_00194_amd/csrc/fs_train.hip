@@ -137,6 +137,19 @@ train_hot_bin_kernel(const uint8_t *__restrict__ bins, int n_rows, int64_t r_pad
         hot_bin[f] = s_arg[0];
 }
 
+// Rows of the longest program (sizes the curvature sums).
+__global__ void __launch_bounds__(256)
+train_max_len_kernel(const int32_t *__restrict__ prog_off, int n_programs, int32_t *__restrict__ out)
+{
+    int m = 0;
+    for (int p = blockIdx.x * blockDim.x + threadIdx.x; p < n_programs; p += gridDim.x * blockDim.x)
+        m = max(m, prog_off[p + 1] - prog_off[p]);
+    for (int off = 32; off > 0; off >>= 1)
+        m = max(m, __shfl_down(m, off));
+    if ((threadIdx.x & 63) == 0)
+        atomicMax(out, m);
+}
+
 __global__ void train_fill_kernel(float *p, int64_t n, float v)
 {
     for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n;
@@ -305,11 +318,14 @@ __device__ __forceinline__ void wave_best_cut(const TrainDesc &d, const Params &
 // train_split_kernel does the search.
 constexpr int kHistSlots = 8;
 
+// HT: type of the curvature sums in LDS.  A bin can hold up to (rows of the slab) x (rows of the
+// longest program); the host picks 64-bit sums when that may pass 2^32.
+template <class HT>
 __global__ void __launch_bounds__(kHistThreads)
 train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, int rows_per_slab,
                   int n_slabs, Params prm)
 {
-    extern __shared__ unsigned long long lds_hist[];            // G: [pairs][256] u64, then H u32
+    extern __shared__ unsigned long long lds_hist[];            // G: [pairs][256] u64, then H: HT
     const TrainDesc &d = descs[blockIdx.z / passes];
     const int pass = blockIdx.z % passes;
     const int row0 = blockIdx.x * rows_per_slab;
@@ -322,10 +338,10 @@ train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, in
     const int slots = min(kHistSlots, n_slots);
     const int node0 = n_slots - 1 + pass * slots;               // heap index of slot 0
     const int pairs = slots * 4;
-    unsigned int *lds_h = (unsigned int *)(lds_hist + pairs * kBins);
+    HT *lds_h = (HT *)(lds_hist + pairs * kBins);
     for (int i = threadIdx.x; i < pairs * kBins; i += kHistThreads) {
         lds_hist[i] = 0ull;
-        lds_h[i] = 0u;
+        lds_h[i] = (HT)0;
     }
     int hot[4];
 #pragma unroll
@@ -356,7 +372,7 @@ train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, in
                     continue;                                    // rebuilt from the node's total
                 const int at = (slot[u] * 4 + fi) * kBins + b;
                 atomicAdd(&lds_hist[at], (unsigned long long)(long long)qh[u].x);
-                atomicAdd(&lds_h[at], (unsigned int)qh[u].y);
+                atomicAdd(&lds_h[at], (HT)qh[u].y);
             }
         }
     }
@@ -383,12 +399,12 @@ train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, in
     for (int i = threadIdx.x; i < pairs * kBins; i += kHistThreads) {
         const int pair = i / kBins, b = i - pair * kBins;
         const int slot = pair >> 2, fi = pair & 3;
-        const unsigned int h = lds_h[i];
-        if (fi >= nf || h == 0u)
+        const unsigned long long h = (unsigned long long)lds_h[i];
+        if (fi >= nf || h == 0ull)
             continue;
         const int64_t at = (((int64_t)(pass * slots + slot) * d.n_features + (f0 + fi)) * kBins + b) * 2;
         atomicAdd(&d.hist[at], lds_hist[i]);
-        atomicAdd(&d.hist[at + 1], (unsigned long long)h);
+        atomicAdd(&d.hist[at + 1], h);
     }
 }
 
@@ -591,6 +607,7 @@ struct fs_trainer {
     int device;
     int max_depth, max_trees;
     int trees_enqueued;
+    int max_len;              // rows of the longest program
     std::vector<void *> allocs;
 };
 
@@ -779,6 +796,19 @@ extern "C" int fs_trainer_create(fs_trainer **out, int32_t n_features, const flo
                            (int64_t)hist_slots * n_features * kBins * 4, 0.0f);
         rc = check_launch("trainer set-up kernels launch");
     }
+    if (rc == FS_OK) {
+        // counters[3] is free until training starts: longest program, read back here
+        hipLaunchKernelGGL(train_max_len_kernel, dim3(256), dim3(256), 0, stream,
+                           (const int32_t *)d_prog_off, n_programs, h.counters + 3);
+        rc = check_launch("train_max_len_kernel launch");
+        if (rc == FS_OK) {
+            e = hipStreamSynchronize(stream);
+            if (e == hipSuccess)
+                e = hipMemcpy(&t->max_len, h.counters + 3, sizeof(int32_t), hipMemcpyDeviceToHost);
+            if (e != hipSuccess)
+                rc = fail_hip(e, "fs_trainer_create: reading the longest program");
+        }
+    }
     if (rc != FS_OK) {
         fs_trainer_destroy(t);
         return rc;
@@ -867,7 +897,7 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
         return fail(FS_EINVAL, "fs_train_boost: grad_scale must be a power of two");
     if (n_trainers == 0 || n_rounds == 0)
         return FS_OK;
-    int max_rows = 0, max_prog = 0, max_feat = 0;
+    int max_rows = 0, max_prog = 0, max_feat = 0, max_len = 0;
     for (int i = 0; i < n_trainers; ++i) {
         const fs_trainer *t = trainers[i];
         if (p->max_depth > t->max_depth)
@@ -878,6 +908,7 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
         if (t->h.n_rows > max_rows) max_rows = t->h.n_rows;
         if (t->h.n_programs > max_prog) max_prog = t->h.n_programs;
         if (t->h.n_features > max_feat) max_feat = t->h.n_features;
+        if (t->max_len > max_len) max_len = t->max_len;
     }
     std::lock_guard<std::mutex> lock(g_train_mu);
     const TrainDesc *d = nullptr;
@@ -895,13 +926,16 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
     prm.max_depth = p->max_depth;
 
     static bool hist_configured[16] = {};
-    const size_t hist_lds = (size_t)kHistSlots * 4 * kBins * 12;
     {
         int dev = 0;
         FS_HIP(hipGetDevice(&dev));
         if (!hist_configured[dev]) {
-            FS_HIP(hipFuncSetAttribute((const void *)train_hist_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)hist_lds));
+            FS_HIP(hipFuncSetAttribute((const void *)train_hist_kernel<unsigned int>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kHistSlots * 4 * kBins * 12));
+            FS_HIP(hipFuncSetAttribute((const void *)train_hist_kernel<unsigned long long>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kHistSlots * 4 * kBins * 16));
             hist_configured[dev] = true;
         }
     }
@@ -916,6 +950,9 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
     }
     const int n_slabs = (max_rows + slab_rows - 1) / slab_rows;
     const int rows_per_slab = (((max_rows + n_slabs - 1) / n_slabs) + 63) & ~63;
+    // 32-bit curvature sums in LDS unless a bin of a slab could pass 2^32
+    const bool wide_h = (long long)max_len * (long long)(rows_per_slab < max_rows ? rows_per_slab : max_rows) >=
+                        ((long long)1 << 32);
     for (int round = 0; round < n_rounds; ++round) {
         prof_start(kKernTrainOther, stream);
         hipLaunchKernelGGL(train_begin_tree_kernel, dim3(nt), dim3(512), 0, stream, d);
@@ -926,10 +963,16 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
             const int n_slots = 1 << level;
             const int slots = n_slots < kHistSlots ? n_slots : kHistSlots;
             const int passes = n_slots / slots;
-            const size_t lds = (size_t)slots * 4 * kBins * 12;
+            const dim3 hgrid((unsigned)n_slabs, (unsigned)((max_feat + 3) / 4), nt * passes);
             prof_start(kKernTrainHist, stream);
-            hipLaunchKernelGGL(train_hist_kernel, dim3((unsigned)n_slabs, (unsigned)((max_feat + 3) / 4), nt * passes),
-                               dim3(kHistThreads), lds, stream, d, level, passes, rows_per_slab, n_slabs, prm);
+            if (wide_h)
+                hipLaunchKernelGGL(train_hist_kernel<unsigned long long>, hgrid, dim3(kHistThreads),
+                                   (size_t)slots * 4 * kBins * 16, stream, d, level, passes, rows_per_slab,
+                                   n_slabs, prm);
+            else
+                hipLaunchKernelGGL(train_hist_kernel<unsigned int>, hgrid, dim3(kHistThreads),
+                                   (size_t)slots * 4 * kBins * 12, stream, d, level, passes, rows_per_slab,
+                                   n_slabs, prm);
             prof_stop(stream);
             prof_start(kKernTrainSplit, stream);
             if (n_slabs > 1)

@@ -150,3 +150,17 @@ def test_random_training_shapes_and_parameters(api, T, seed):
           eta=float(rng.choice([0.1, 0.5, 1.0])), lam=float(rng.choice([0.0, 1.0, 7.5])),
           min_child_weight=float(rng.choice([0.0, 1.0, 20.0])),
           min_gain=float(rng.choice([0.0, 0.0, 0.01])))
+
+
+def test_one_very_long_program_does_not_overflow_the_curvature_sums(api, T):
+    """Curvature of a row = rows of its program, so one program of 66 000 rows puts
+    66 000 x 66 000 > 2^32 into a single histogram bin; also more rows than one slab."""
+    rng = np.random.default_rng(5)
+    lens = np.concatenate([[66_000], rng.integers(1, 9, 60)]).astype(np.int64)
+    off = np.zeros(lens.shape[0] + 1, np.int64)
+    np.cumsum(lens, out=off[1:])
+    X = W.draw_features(rng, int(off[-1]), 0.5, n_features=4)
+    y = rng.standard_normal(lens.shape[0]).astype(np.float32)
+    cut_off, cuts = W.draw_cuts(X, 7)
+    ts = W.TrainSet(X, off.astype(np.int32), y, cut_off, cuts)
+    check(api, T, ts, rounds=2, max_depth=2, eta=0.5, lam=1.0)
