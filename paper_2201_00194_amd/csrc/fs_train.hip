@@ -219,18 +219,25 @@ train_grad_kernel(const TrainDesc *__restrict__ descs, float grad_scale, int wit
     }
 }
 
+// The node's own term of the gain, g*g/(H+lambda): the same for every cut of the node, so it is
+// divided once per (node, feature) and not once per cut.
+__device__ __forceinline__ double parent_term(long long G, long long H, double inv_scale, double lambda)
+{
+    const double g = (double)G * inv_scale;
+    double t3 = g * g;
+    t3 = t3 / ((double)H + lambda);
+    return t3;
+}
+
 __device__ __forceinline__ double split_gain(long long GL, long long HL, long long G, long long H,
-                                             double inv_scale, double lambda)
+                                             double inv_scale, double lambda, double t3)
 {
     const long long GR = G - GL, HR = H - HL;
-    const double gl = (double)GL * inv_scale, gr = (double)GR * inv_scale,
-                 g = (double)G * inv_scale;
+    const double gl = (double)GL * inv_scale, gr = (double)GR * inv_scale;
     double t1 = gl * gl;
     t1 = t1 / ((double)HL + lambda);
     double t2 = gr * gr;
     t2 = t2 / ((double)HR + lambda);
-    double t3 = g * g;
-    t3 = t3 / ((double)H + lambda);
     return (t1 + t2) - t3;
 }
 
@@ -273,6 +280,7 @@ __device__ __forceinline__ void wave_best_cut(const TrainDesc &d, const Params &
     }
     const long long before_g = pg - g[3], before_h = ph - h[3];
     const int m = d.cut_off[f + 1] - d.cut_off[f];
+    const double t3 = parent_term(G, H, prm.inv_scale, prm.lambda);
     int cut = 0;
     double gain = 0.0;
     long long bGL = 0, bHL = 0;
@@ -281,7 +289,7 @@ __device__ __forceinline__ void wave_best_cut(const TrainDesc &d, const Params &
         const long long GL = before_g + g[k], HL = before_h + h[k];
         const int j = 4 * lane + k + 1;
         if (j <= m && HL >= prm.mcw && H - HL >= prm.mcw) {
-            const double gn = split_gain(GL, HL, G, H, prm.inv_scale, prm.lambda);
+            const double gn = split_gain(GL, HL, G, H, prm.inv_scale, prm.lambda, t3);
             if (cut == 0 || gn > gain) {                         // ascending cuts: first of equals stays
                 gain = gn;
                 cut = j;
