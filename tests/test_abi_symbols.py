@@ -114,3 +114,44 @@ def test_trainer_argument_errors_need_no_gpu():
     lib.fs_train_boost.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
                                    ctypes.c_void_p]
     assert lib.fs_train_boost(-1, None, 1, None, None) == -1
+
+
+def test_headers_compile_as_c99_and_link(tmp_path):
+    """The installed headers are plain C: a C99 program that includes both, fills the structs
+    and calls argument-checking paths builds with -pedantic -Werror and runs without a GPU."""
+    import subprocess
+    if not os.path.exists(LIB):
+        from paper_2201_00194_amd import build
+        build.build()
+    src = tmp_path / "abi.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "familyseer.h"
+#include "familyseer_train.h"
+int main(void) {
+    fs_family fam;
+    fs_topk_req req;
+    fs_gather_src gs;
+    fs_train_params tp;
+    memset(&fam, 0, sizeof fam); memset(&req, 0, sizeof req); memset(&gs, 0, sizeof gs);
+    memset(&tp, 0, sizeof tp);
+    if (fs_version() < 100) return 1;
+    if (fs_score_families(-1, &fam, NULL) != FS_EINVAL) return 2;
+    if (strlen(fs_last_error()) == 0) return 3;
+    req.k = FS_MAX_TOPK + 1;
+    if (fs_topk(1, &req, NULL) != FS_EUNSUPPORTED) return 4;
+    if (fs_colblock64_floats(65, 3) != 2 * 3 * 64) return 5;
+    if (fs_train_boost(-1, NULL, 1, &tp, NULL) != FS_EINVAL) return 6;
+    if (fs_gather_programs(0, 1, &gs, NULL, 0, NULL, 0, NULL, NULL, NULL, NULL) != FS_EINVAL) return 7;
+    printf("ok %d %d\n", FS_TRAIN_MAX_DEPTH, FS_KERNEL_CLASSES);
+    return 0;
+}
+''')
+    exe = tmp_path / "abi"
+    libdir = os.path.dirname(LIB)
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
+                    "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-lfamilyseer", "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    assert out.startswith("ok 8 10")
