@@ -36,7 +36,7 @@
 extern "C" {
 #endif
 
-#define FS_TRAIN_MAX_DEPTH 8   /* split levels per tree                                  */
+#define FS_TRAIN_MAX_DEPTH 10  /* split levels per tree                                  */
 #define FS_TRAIN_MAX_CUTS 255  /* cut points per feature (bins fit a byte)               */
 
 typedef struct fs_trainer fs_trainer; /* opaque: one family's training set and model so far */

@@ -293,7 +293,7 @@ class DeviceFamily:
 
 # ---- training (familyseer_train.h) -------------------------------------------------------------
 
-FS_TRAIN_MAX_DEPTH = 8
+FS_TRAIN_MAX_DEPTH = 10
 FS_TRAIN_MAX_CUTS = 255
 
 

@@ -30,7 +30,7 @@
 
 namespace fs {
 
-constexpr int kHeapNodes = (1 << (FS_TRAIN_MAX_DEPTH + 1)) - 1;   // 511
+constexpr int kHeapNodes = (1 << (FS_TRAIN_MAX_DEPTH + 1)) - 1;   // 2047
 constexpr int kBins = FS_TRAIN_MAX_CUTS + 1;                      // 256
 constexpr int kHistThreads = 1024;
 constexpr int kHistRowsPerSlab = 65536;
@@ -454,6 +454,7 @@ train_split_kernel(const TrainDesc *__restrict__ descs, int level, Params prm)
 // decides.
 constexpr int kPickThreads = 1024;
 constexpr int kMaxSlots = 1 << FS_TRAIN_MAX_DEPTH;
+static_assert(kMaxSlots <= kPickThreads, "one thread per node of the deepest level");
 
 __global__ void __launch_bounds__(kPickThreads)
 train_pick_kernel(const TrainDesc *__restrict__ descs, int level, Params prm)
@@ -740,7 +741,7 @@ extern "C" int fs_trainer_create(fs_trainer **out, int32_t n_features, const flo
     TRY(dev_alloc(t, &h.prog_pred, (size_t)n_programs));
     TRY(dev_alloc(t, &h.qh, (size_t)n_rows));
     TRY(dev_alloc(t, &h.node_of_row, (size_t)n_rows));
-    TRY(dev_alloc(t, &h.hist, (size_t)hist_slots * n_features * kBins * 2));
+    h.hist = nullptr;       // only families that span several slabs need it: see ensure_hist
     TRY(dev_alloc(t, &h.h_state, (size_t)kHeapNodes));
     TRY(dev_alloc(t, &h.h_feat, (size_t)kHeapNodes));
     TRY(dev_alloc(t, &h.h_cut, (size_t)kHeapNodes));
@@ -799,9 +800,6 @@ extern "C" int fs_trainer_create(fs_trainer **out, int32_t n_features, const flo
                            (const uint8_t *)bins, (int)n_rows, h.r_pad, d_hot);
         hipLaunchKernelGGL(train_fill_kernel, dim3(1024), dim3(256), 0, stream, h.row_pred,
                            (int64_t)n_rows, bias);
-        // the histogram buffer starts all zero; the split kernel clears what it reads
-        hipLaunchKernelGGL(train_fill_kernel, dim3(1024), dim3(256), 0, stream, (float *)h.hist,
-                           (int64_t)hist_slots * n_features * kBins * 4, 0.0f);
         rc = check_launch("trainer set-up kernels launch");
     }
     if (rc == FS_OK) {
@@ -823,6 +821,22 @@ extern "C" int fs_trainer_create(fs_trainer **out, int32_t n_features, const flo
     }
     *out = t;
     return FS_OK;
+}
+
+// The global histogram buffer of a trainer whose rows span several slabs, all zero at first
+// (the split kernel clears what it reads).
+static int ensure_hist(fs_trainer *t, hipStream_t stream)
+{
+    if (t->h.hist)
+        return FS_OK;
+    const size_t slots = t->max_depth > 0 ? (size_t)1 << (t->max_depth - 1) : 1;
+    const size_t words = slots * (size_t)t->h.n_features * kBins * 2;
+    int rc = dev_alloc(t, &t->h.hist, words);
+    if (rc != FS_OK)
+        return rc;
+    hipLaunchKernelGGL(train_fill_kernel, dim3(1024), dim3(256), 0, stream, (float *)t->h.hist,
+                       (int64_t)words * 2, 0.0f);
+    return check_launch("train_fill_kernel launch");
 }
 
 // Uploads the batch's descriptors; returns the device array.
@@ -919,6 +933,20 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
         if (t->max_len > max_len) max_len = t->max_len;
     }
     std::lock_guard<std::mutex> lock(g_train_mu);
+    int slab_rows = kHistRowsPerSlab;
+    if (const char *e = getenv("FS_TUNE_TRAIN_SLAB_ROWS")) {     // tuning / test aid
+        const int v = atoi(e);
+        if (v >= 64 && v <= kHistRowsPerSlab)
+            slab_rows = v;
+    }
+    // one slab per family up to slab_rows rows: the histogram workgroup then searches the cuts
+    // itself and nothing is added up in global memory
+    const int n_slabs = (max_rows + slab_rows - 1) / slab_rows;
+    if (n_slabs > 1)
+        for (int i = 0; i < n_trainers && rc == FS_OK; ++i)
+            rc = ensure_hist(trainers[i], stream);
+    if (rc != FS_OK)
+        return rc;
     const TrainDesc *d = nullptr;
     rc = upload_batch(n_trainers, trainers, stream, &d);
     if (rc != FS_OK)
@@ -949,14 +977,6 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
     }
     const unsigned nt = (unsigned)n_trainers;
     const unsigned row_blocks = (unsigned)((max_rows + 255) / 256);
-    // one slab per family up to kHistRowsPerSlab rows: histograms are then stored, not added
-    int slab_rows = kHistRowsPerSlab;
-    if (const char *e = getenv("FS_TUNE_TRAIN_SLAB_ROWS")) {     // tuning / test aid
-        const int v = atoi(e);
-        if (v >= 64 && v <= kHistRowsPerSlab)
-            slab_rows = v;
-    }
-    const int n_slabs = (max_rows + slab_rows - 1) / slab_rows;
     const int rows_per_slab = (((max_rows + n_slabs - 1) / n_slabs) + 63) & ~63;
     // 32-bit curvature sums in LDS unless a bin of a slab could pass 2^32
     const bool wide_h = (long long)max_len * (long long)(rows_per_slab < max_rows ? rows_per_slab : max_rows) >=

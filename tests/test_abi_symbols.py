@@ -106,7 +106,7 @@ def test_trainer_argument_errors_need_no_gpu():
     good = (ctypes.c_float * 3)(0.25, 0.5, 1.0)
     assert create(cu=good, nf=0) == -1
     assert create(cu=good, rows=0) == -1
-    assert create(cu=good, depth=9) == -4                     # FS_EUNSUPPORTED
+    assert create(cu=good, depth=11) == -4                    # FS_EUNSUPPORTED
     assert create(cu=good, trees=0) == -1
     assert create(cu=good, layout=7) == -1
     assert out.value is None
@@ -154,4 +154,4 @@ int main(void) {
                     "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
                     "-L", libdir, "-lfamilyseer", "-Wl,-rpath," + libdir], check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
-    assert out.startswith("ok 8 10")
+    assert out.startswith("ok 10 10")

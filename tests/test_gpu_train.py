@@ -65,6 +65,20 @@ def test_full_width_features_255_cuts_depth8(api, T):
     check(api, T, ts, rounds=3, max_depth=8, eta=0.3, lam=0.5, bias=0.25)
 
 
+def test_deepest_trees(api, T):
+    ts = W.make_train_set(24, 3000, stmts=(1, 6), n_features=12, max_cuts=255)
+    tr, exp = check(api, T, ts, rounds=2, max_depth=api.FS_TRAIN_MAX_DEPTH, eta=0.5, lam=0.0)
+    depth = 0                                    # the oracle's first tree really is that deep
+    a, b = exp.tree_off[0], exp.tree_off[1]
+    level = {0: 0}
+    for n in range(b - a):
+        if exp.split_feature[a + n] >= 0:
+            level[int(exp.left[a + n])] = level[int(exp.right[a + n])] = level[n] + 1
+            depth = max(depth, level[n] + 1)
+    assert depth == api.FS_TRAIN_MAX_DEPTH
+    check(api, T, ts, rounds=1, max_depth=9, eta=0.5, lam=1.0)
+
+
 def test_regularisation_and_stopping_rules(api, T):
     ts = W.make_train_set(23, 400, stmts=(1, 5), n_features=9, max_cuts=15)
     check(api, T, ts, rounds=3, max_depth=4, eta=1.0, lam=0.0)
@@ -146,7 +160,7 @@ def test_random_training_shapes_and_parameters(api, T, seed):
                           n_features=nf, max_cuts=int(rng.choice([1, 2, 7, 64, 255])),
                           zero_frac=float(rng.choice([0.0, 0.3, 0.95])))
     check(api, T, ts, rounds=int(rng.integers(1, 6)), layout=int(rng.integers(0, 2)),
-          bias=float(rng.choice([0.0, 1.5])), max_depth=int(rng.integers(0, 9)),
+          bias=float(rng.choice([0.0, 1.5])), max_depth=int(rng.integers(0, 11)),
           eta=float(rng.choice([0.1, 0.5, 1.0])), lam=float(rng.choice([0.0, 1.0, 7.5])),
           min_child_weight=float(rng.choice([0.0, 1.0, 20.0])),
           min_gain=float(rng.choice([0.0, 0.0, 0.01])))
@@ -164,3 +178,20 @@ def test_one_very_long_program_does_not_overflow_the_curvature_sums(api, T):
     cut_off, cuts = W.draw_cuts(X, 7)
     ts = W.TrainSet(X, off.astype(np.int32), y, cut_off, cuts)
     check(api, T, ts, rounds=2, max_depth=2, eta=0.5, lam=1.0)
+
+
+def test_many_tied_and_near_tied_cuts(api, T):
+    """Small integer features in duplicated columns and coarse targets make many cuts tie
+    exactly or differ in the last bits: the choice must still be the oracle's first largest."""
+    rng = np.random.default_rng(8)
+    base = rng.integers(0, 6, size=(600, 3)).astype(np.float32)
+    X = np.concatenate([base, base, base[:, ::-1]], axis=1)          # 9 columns, 3 distinct twice
+    off = np.arange(601, dtype=np.int32)
+    y = rng.integers(-2, 3, 600).astype(np.float32)
+    cut_off, cuts = W.draw_cuts(X, 255)
+    ts = W.TrainSet(X, off, y, cut_off, cuts)
+    check(api, T, ts, rounds=6, max_depth=6, eta=1.0, lam=0.0)
+    check(api, T, ts, rounds=3, max_depth=5, eta=0.3, lam=2.0, grad_scale=float(1 << 4))
+    big = W.TrainSet(X * np.float32(3e4), off, (y * np.float32(1000)).astype(np.float32),
+                     *W.draw_cuts(X * np.float32(3e4), 255))
+    check(api, T, big, rounds=3, max_depth=4, eta=0.5, lam=0.0, grad_scale=float(1 << 20))
