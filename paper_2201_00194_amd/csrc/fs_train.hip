@@ -640,6 +640,10 @@ static int dev_alloc(fs_trainer *t, T **out, size_t count)
     if (e != hipSuccess)
         return e == hipErrorOutOfMemory ? fail(FS_ENOMEM, "hipMalloc of %zu bytes failed", count * sizeof(T))
                                         : fail_hip(e, "hipMalloc");
+    if (t->allocs.size() == t->allocs.capacity()) {       // cannot happen with the reserve at creation
+        (void)hipFree(p);
+        return fail(FS_ENOMEM, "allocation table full");
+    }
     t->allocs.push_back(p);
     *out = (T *)p;
     return FS_OK;
@@ -706,6 +710,12 @@ extern "C" int fs_trainer_create(fs_trainer **out, int32_t n_features, const flo
     fs_trainer *t = new (std::nothrow) fs_trainer();
     if (!t)
         return fail(FS_ENOMEM, "out of host memory");
+    try {
+        t->allocs.reserve(64);      // every later push_back stays within this (no throw past the C ABI)
+    } catch (const std::bad_alloc &) {
+        delete t;
+        return fail(FS_ENOMEM, "out of host memory");
+    }
     int rc = FS_OK;
     hipError_t e = hipGetDevice(&t->device);
     if (e != hipSuccess) {
