@@ -463,34 +463,71 @@ extern "C" int fs_topk(int32_t n_requests, const fs_topk_req *reqs, void *stream
     int rc = current_ctx(&ctx);
     if (rc != FS_OK)
         return rc;
-    // Long requests are cut into slices (one workgroup each) whose candidates a second
-    // kernel merges; the others take one workgroup and finish in the first kernel.
-    auto slices_of = [](const fs_topk_req &r) {
+    // Three ways to serve a request:
+    //   0  one workgroup, finished by the first kernel;
+    //   1  long request, k <= 4096: slices (one workgroup each) leave their best k in scratch and
+    //      one workgroup merges them in LDS;
+    //   2  long request with a wider cut: slices of about kTopkWideSlice entries leave their best
+    //      min(k, length) sorted, then pairwise merges in global memory, level by level.
+    struct Plan { int mode, s, per; };
+    auto plan_of = [](const fs_topk_req &r) {
+        Plan p = {0, 1, r.n};
         if (r.n < kTopkSliceMin || r.k == 0)
-            return 1;
+            return p;
         int kp = 1;
         while (kp < r.k)
             kp <<= 1;
+        if (kp > kTopkMergeCap / 4) {
+            int s = (r.n + kTopkWideSlice - 1) / kTopkWideSlice;
+            if (s > kTopkWideMaxSlices)
+                s = kTopkWideMaxSlices;
+            if (s >= 2) {
+                p.mode = 2;
+                p.s = s;
+                p.per = (((r.n + s - 1) / s) + 63) & ~63;
+            }
+            return p;
+        }
         int s = kTopkMergeCap / kp;
         if (s > kTopkMaxSlices)
             s = kTopkMaxSlices;
         if (s > r.n / kTopkSliceEntries)
             s = r.n / kTopkSliceEntries;
-        return s >= 2 ? s : 1;
+        if (s >= 2) {
+            p.mode = 1;
+            p.s = s;
+            p.per = (((r.n + s - 1) / s) + 63) & ~63;
+        }
+        return p;
     };
-    size_t n_blocks = 0, n_merge = 0, comp_total = 0;
-    int max_comp = 0;
+    // sizes: first-stage workgroups, LDS merges, merge-path pairs per level, scratch composites
+    size_t n_blocks = 0, n_merge = 0, comp_total = 0, n_pairs_total = 0;
+    int max_comp = 0, n_levels = 0;
     for (int i = 0; i < n_requests; ++i) {
-        const int s = slices_of(reqs[i]);
-        n_blocks += (size_t)s;
-        if (s > 1) {
+        const fs_topk_req &r = reqs[i];
+        const Plan p = plan_of(r);
+        n_blocks += (size_t)p.s;
+        if (p.mode == 1) {
             ++n_merge;
-            comp_total += (size_t)s * (size_t)reqs[i].k;
+            comp_total += (size_t)p.s * (size_t)r.k;
             int kp = 1;
-            while (kp < reqs[i].k)
+            while (kp < r.k)
                 kp <<= 1;
-            if (s * kp > max_comp)
-                max_comp = s * kp;
+            if (p.s * kp > max_comp)
+                max_comp = p.s * kp;
+        } else if (p.mode == 2) {
+            comp_total += (size_t)r.n;                       // first-stage lists: at most every entry
+            int lists = p.s, levels = 0;
+            while (lists > 1) {
+                const int pairs = lists / 2;
+                n_pairs_total += (size_t)pairs;
+                if (lists > 2)
+                    comp_total += (size_t)pairs * (size_t)r.k;   // merged lists (the last level writes the answer)
+                lists = pairs + (lists & 1);
+                ++levels;
+            }
+            if (levels > n_levels)
+                n_levels = levels;
         }
     }
     if (comp_total) {
@@ -500,43 +537,115 @@ extern "C" int fs_topk(int32_t n_requests, const fs_topk_req *reqs, void *stream
     }
     const size_t desc_bytes = sizeof(TopkDesc) * n_blocks;
     const size_t merge_off = (desc_bytes + 15) & ~(size_t)15;
-    const size_t total_bytes = merge_off + sizeof(TopkMergeDesc) * n_merge;
+    const size_t path_off = (merge_off + sizeof(TopkMergeDesc) * n_merge + 15) & ~(size_t)15;
+    const size_t total_bytes = path_off + sizeof(TopkPairDesc) * n_pairs_total;
     Slot *slot = nullptr;
     rc = acquire_slot(ctx, total_bytes, &slot);
     if (rc != FS_OK)
         return rc;
     TopkDesc *h = (TopkDesc *)slot->h_buf;
     TopkMergeDesc *hm = (TopkMergeDesc *)((char *)slot->h_buf + merge_off);
+    TopkPairDesc *hp = (TopkPairDesc *)((char *)slot->h_buf + path_off);
     unsigned long long *comp = (unsigned long long *)ctx->scratch;
+    // merge-path descriptors are stored level by level: first count the pairs of every level
+    constexpr int kMaxLevels = 8;
+    size_t level_pairs[kMaxLevels] = {0}, level_at[kMaxLevels] = {0};
+    int level_entries[kMaxLevels] = {0};        // longest la + lb of the level: sizes its grid
+    for (int i = 0; i < n_requests; ++i) {
+        const Plan p = plan_of(reqs[i]);
+        if (p.mode != 2)
+            continue;
+        int lists = p.s, lv = 0;
+        while (lists > 1) {
+            level_pairs[lv++] += (size_t)(lists / 2);
+            lists = lists / 2 + (lists & 1);
+        }
+    }
+    for (int lv = 1; lv < kMaxLevels; ++lv)
+        level_at[lv] = level_at[lv - 1] + level_pairs[lv - 1];
+    size_t level_fill[kMaxLevels];
+    for (int lv = 0; lv < kMaxLevels; ++lv)
+        level_fill[lv] = level_at[lv];
     size_t b = 0, m = 0;
     for (int i = 0; i < n_requests; ++i) {
         const fs_topk_req &r = reqs[i];
-        const int s = slices_of(r);
-        const int per = s > 1 ? (((r.n + s - 1) / s) + 63) & ~63 : r.n;
-        for (int j = 0; j < s; ++j, ++b) {
+        const Plan p = plan_of(r);
+        // lists of a mode-2 request: pointer and length of every current list
+        const unsigned long long *list_ptr[kTopkWideMaxSlices];
+        int list_len[kTopkWideMaxSlices];
+        unsigned long long *first = comp;
+        for (int j = 0; j < p.s; ++j, ++b) {
             h[b].score = r.score;
             h[b].out_idx = r.out_idx;
             h[b].out_score = r.out_score;
             h[b].n = r.n;
             h[b].k = r.k;
-            const long long lo = (long long)j * per, hi = lo + per;
+            const long long lo = (long long)j * p.per, hi = lo + p.per;
             h[b].sub_begin = (int32_t)(lo < r.n ? lo : r.n);
             h[b].sub_end = (int32_t)(hi < r.n ? hi : r.n);
-            h[b].comp_out = s > 1 ? comp + (size_t)j * (size_t)r.k : nullptr;
+            h[b].comp_pad = p.mode == 1 ? 1 : 0;
+            h[b].pad = 0;
+            if (p.mode == 0) {
+                h[b].comp_out = nullptr;
+            } else if (p.mode == 1) {
+                h[b].comp_out = comp + (size_t)j * (size_t)r.k;
+            } else {
+                const int len = h[b].sub_end - h[b].sub_begin;
+                h[b].comp_out = comp;
+                list_ptr[j] = comp;
+                list_len[j] = len < r.k ? len : r.k;
+                comp += (size_t)list_len[j];
+            }
         }
-        if (s > 1) {
-            hm[m].comp_in = comp;
+        if (p.mode == 1) {
+            hm[m].comp_in = first;
             hm[m].score = r.score;
             hm[m].out_idx = r.out_idx;
             hm[m].out_score = r.out_score;
-            hm[m].n_comp = s * r.k;
+            hm[m].n_comp = p.s * r.k;
             hm[m].n = r.n;
             hm[m].k = r.k;
             hm[m].pad = 0;
-            comp += (size_t)s * (size_t)r.k;
+            comp += (size_t)p.s * (size_t)r.k;
             ++m;
+        } else if (p.mode == 2) {
+            int lists = p.s, lv = 0;
+            while (lists > 1) {
+                const int pairs = lists / 2;
+                for (int q = 0; q < pairs; ++q) {
+                    TopkPairDesc &t = hp[level_fill[lv]++];
+                    t.a = list_ptr[2 * q];
+                    t.b = list_ptr[2 * q + 1];
+                    t.la = list_len[2 * q];
+                    t.lb = list_len[2 * q + 1];
+                    const long long both = (long long)t.la + t.lb;
+                    if (both > level_entries[lv])
+                        level_entries[lv] = (int)both;
+                    t.lo = (int32_t)(both < r.k ? both : r.k);
+                    t.k = r.k;
+                    t.score = r.score;
+                    t.out_idx = r.out_idx;
+                    t.out_score = r.out_score;
+                    if (lists == 2) {
+                        t.out = nullptr;                      // last level: the answer itself
+                    } else {
+                        t.out = comp;
+                        comp += (size_t)r.k;
+                    }
+                    list_ptr[q] = t.out;
+                    list_len[q] = t.lo;
+                }
+                if (lists & 1) {                              // odd one out moves up as it is
+                    list_ptr[pairs] = list_ptr[lists - 1];
+                    list_len[pairs] = list_len[lists - 1];
+                }
+                lists = pairs + (lists & 1);
+                ++lv;
+            }
         }
     }
+    if ((size_t)(comp - (unsigned long long *)ctx->scratch) > comp_total || b != n_blocks || m != n_merge)
+        return fail(FS_EDEVICE, "fs_topk: internal plan mismatch");
     FS_HIP(hipMemcpyAsync(slot->d_buf, slot->h_buf, total_bytes, hipMemcpyHostToDevice, stream));
     slot->used = true;
     prof_start(kKernTopk, stream);
@@ -544,6 +653,9 @@ extern "C" int fs_topk(int32_t n_requests, const fs_topk_req *reqs, void *stream
     if (rc == FS_OK && n_merge)
         rc = launch_topk_merge((const TopkMergeDesc *)((const char *)slot->d_buf + merge_off),
                                (int)n_merge, max_comp, stream);
+    for (int lv = 0; lv < n_levels && rc == FS_OK; ++lv)
+        rc = launch_topk_pairs((const TopkPairDesc *)((const char *)slot->d_buf + path_off) + level_at[lv],
+                               (int)level_pairs[lv], level_entries[lv], stream);
     prof_stop(stream);
     hipError_t e = hipEventRecord(slot->done, stream);
     if (rc != FS_OK)

@@ -163,7 +163,9 @@ struct TopkDesc {
     int32_t k;
     int32_t sub_begin, sub_end;      // the slice [sub_begin, sub_end) this workgroup ranks
     unsigned long long *comp_out;    // NULL: final answer to out_idx/out_score; else the slice's
-                                     // best k (key, ~index) composites, best first, 0-padded
+                                     // best min(k, slice length) (key, ~index) composites, best first
+    int32_t comp_pad;                // 1: pad comp_out with 0 up to k entries
+    int32_t pad;
 };
 
 // Second stage of a large request: merge the slices' candidates.
@@ -178,6 +180,18 @@ struct TopkMergeDesc {
     int32_t pad;
 };
 
+
+// One merge of two lists of composites (each best first) in global memory: the best `lo` of
+// their union go to `out` (composites), or, at the last level of a request, to its
+// out_idx / out_score (then `lo` = min(n, k) and entries up to k are padded with -1 / -inf).
+struct TopkPairDesc {
+    const unsigned long long *a, *b;
+    unsigned long long *out;       // NULL at the last level
+    const float *score;
+    int32_t *out_idx;
+    float *out_score;              // may be NULL
+    int32_t la, lb, lo, k;
+};
 
 // ---- launchers (each returns FS_OK or records an error) ---------------------------------------
 int launch_traverse_global(const FamDesc *d_desc, int n_families, int total_blocks,
@@ -195,6 +209,9 @@ constexpr int kTopkSliceMin = 8192;      // requests at least this long are spli
 constexpr int kTopkSliceEntries = 2048;  // of at least this many entries
 constexpr int kTopkMaxSlices = 16;
 constexpr int kTopkMergeCap = 16384;     // composites (lists padded to a power of two) the merge holds in LDS
+constexpr int kTopkWideSlice = 2048;     // slice length of cuts too wide for the LDS merge (k > 4096)
+constexpr int kTopkWideMaxSlices = 128;
+int launch_topk_pairs(const TopkPairDesc *d_desc, int n_pairs, int max_entries, hipStream_t stream);
 int launch_retile(const FamDesc *d_desc, int n_families, int total_blocks, hipStream_t stream);
 int launch_pack_colblock64(const float *in, int64_t n_rows, int32_t n_features, float *out,
                            hipStream_t stream);

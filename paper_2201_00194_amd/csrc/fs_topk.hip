@@ -14,9 +14,11 @@
 //      the result is unique.
 // A long request (>= 8192 entries) is cut into up to 16 slices, one workgroup each, which
 // leave their best k composites in scratch, best first; a second kernel merges the slices'
-// lists pairwise in LDS, keeping the best k of every pair, and writes the answer.  The union of the slices' best k holds the
-// request's best k, and composites order the same way everywhere, so nothing changes in the
-// result.
+// lists pairwise in LDS, keeping the best k of every pair, and writes the answer.  The union
+// of the slices' best k holds the request's best k, and composites order the same way
+// everywhere, so nothing changes in the result.  Cuts wider than 4096 do not fit that merge:
+// they are cut into slices of about 2048 entries (up to 128) whose sorted lists are merged
+// pairwise in global memory, level by level, each merge keeping the best k.
 #include "fs_internal.h"
 
 namespace fs {
@@ -61,8 +63,9 @@ topk_kernel(const TopkDesc *__restrict__ descs)
     const uint32_t idx0 = (uint32_t)d.sub_begin;
 
     if (d.comp_out) {
-        for (int j = kk + tid; j < k; j += kTopkThreads)
-            d.comp_out[j] = 0ull;
+        if (d.comp_pad)
+            for (int j = kk + tid; j < k; j += kTopkThreads)
+                d.comp_out[j] = 0ull;
     } else {
         for (int j = kk + tid; j < k; j += kTopkThreads) {
             d.out_idx[j] = -1;
@@ -288,6 +291,68 @@ topk_merge_kernel(const TopkMergeDesc *__restrict__ descs)
                 d.out_score[j] = -__builtin_inff();
         }
     }
+}
+
+// Merge of two descending lists of composites that live in global memory, for cuts too wide
+// for the LDS merge.  All composites differ, so an entry's place in the merged list is its own
+// position plus the number of entries of the other list that exceed it: one thread per entry
+// finds that count by bisection and stores the entry if its place is among the best `lo`.
+// blockIdx.y names the pair, blockIdx.x a run of kTopkThreads entries of (a then b).
+__global__ void __launch_bounds__(kTopkThreads)
+topk_pair_kernel(const TopkPairDesc *__restrict__ descs)
+{
+    const TopkPairDesc d = descs[blockIdx.y];
+    const int e = blockIdx.x * kTopkThreads + threadIdx.x;
+    if (e < d.la + d.lb) {
+        const bool in_a = e < d.la;
+        const unsigned long long *__restrict__ self = in_a ? d.a : d.b;
+        const unsigned long long *__restrict__ other = in_a ? d.b : d.a;
+        const int me = in_a ? e : e - d.la;
+        if (me < d.lo) {
+            const unsigned long long v = self[me];
+            // entries of `other` above v, counted no further than would push v out of the cut
+            int lo = 0, hi = min(in_a ? d.lb : d.la, d.lo - me);
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (other[mid] > v)
+                    lo = mid + 1;
+                else
+                    hi = mid;
+            }
+            const int p = me + lo;
+            if (p < d.lo) {
+                if (d.out) {
+                    d.out[p] = v;
+                } else {
+                    const uint32_t idx = 0xFFFFFFFFu - (uint32_t)(v & 0xFFFFFFFFull);
+                    d.out_idx[p] = (int32_t)idx;
+                    if (d.out_score)
+                        d.out_score[p] = d.score[idx];
+                }
+            }
+        }
+    }
+    if (!d.out && blockIdx.x == 0) {
+        for (int p = d.lo + threadIdx.x; p < d.k; p += kTopkThreads) {
+            d.out_idx[p] = -1;
+            if (d.out_score)
+                d.out_score[p] = -__builtin_inff();
+        }
+    }
+}
+
+int launch_topk_pairs(const TopkPairDesc *d_desc, int n_pairs, int max_entries, hipStream_t stream)
+{
+    const int runs = max_entries > 0 ? (max_entries + kTopkThreads - 1) / kTopkThreads : 1;
+    constexpr int kMaxY = 32768;             // pairs per launch (grid.y)
+    for (int at = 0; at < n_pairs; at += kMaxY) {
+        const int cnt = n_pairs - at < kMaxY ? n_pairs - at : kMaxY;
+        hipLaunchKernelGGL(topk_pair_kernel, dim3(runs, cnt), dim3(kTopkThreads), 0, stream, d_desc + at);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return fail_hip(e, "topk_pair_kernel launch");
+    }
+    return FS_OK;
 }
 
 int launch_topk_merge(const TopkMergeDesc *d_desc, int n_requests, int max_padded, hipStream_t stream)

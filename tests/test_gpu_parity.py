@@ -227,6 +227,57 @@ def test_topk_long_requests_are_sliced_and_merged(api, oracle):
             assert np.array_equal(ov.cpu().numpy().view(np.uint32), val.view(np.uint32))
 
 
+def test_topk_wide_cuts_merge_in_global_memory(api, oracle):
+    """Cuts above 4096 of long requests: slices sorted per workgroup, then pairwise merges level
+    by level.  Odd slice counts, a last slice shorter than the others, k above the request's
+    length, ties that straddle slices, NaN and signed zeros; mixed with other kinds of request
+    in one submission and repeated so that the scratch is reused."""
+    import torch
+    rng = np.random.default_rng(23)
+    cases = []
+    cases.append((rng.standard_normal(65536).astype(np.float32), 16384))     # 32 slices, 5 levels
+    cases.append((rng.standard_normal(8192).astype(np.float32), 4097))       # 4 slices
+    cases.append((rng.standard_normal(8193).astype(np.float32), 4097))       # 5 slices, the last one shorter
+    cases.append((rng.standard_normal(24577).astype(np.float32), 5000))      # 13 slices, ragged
+    cases.append((rng.standard_normal(20000).astype(np.float32), 16384))     # 10 slices: odd counts carry one list up
+    cases.append((rng.standard_normal(12000).astype(np.float32), 16000))     # k above n: -1 padding
+    cases.append((np.full(70000, 0.5, np.float32), 9000))                    # all tie: lowest indices
+    q = (rng.integers(-2, 3, 300000) / 2.0).astype(np.float32)               # 5 values, 128 slices (the cap)
+    q[rng.integers(0, 300000, 3000)] = np.nan
+    q[rng.integers(0, 300000, 3000)] = -0.0
+    cases.append((q, 12345))
+    step = np.zeros(100000, np.float32)
+    step[93000:] = 2.0                                                       # best entries in the last slices
+    cases.append((step, 8000))
+    cases.append((rng.standard_normal(700000).astype(np.float32), 16384))    # 128 slices of 5504 (cap)
+    cases.append((np.full(9000, np.nan, np.float32), 6000))
+    cases.append((rng.standard_normal(30000).astype(np.float32), 100))       # LDS merge, same launch
+    cases.append((rng.standard_normal(500).astype(np.float32), 20))          # short, same launch
+    reqs, outs = [], []
+    for sc, k in cases:
+        t = torch.from_numpy(sc).cuda()
+        oi = torch.full((k,), -7, dtype=torch.int32, device="cuda")
+        ov = torch.full((k,), float("nan"), dtype=torch.float32, device="cuda")
+        reqs.append(api.TopkRequest(t, sc.shape[0], k, oi, ov))
+        outs.append((oi, ov))
+    for _ in range(2):
+        api.fs_topk(reqs)
+        torch.cuda.synchronize()
+        for (sc, k), (oi, ov) in zip(cases, outs):
+            idx, val = oracle.topk(sc, k)
+            assert np.array_equal(oi.cpu().numpy(), idx), (sc.shape[0], k)
+            assert np.array_equal(ov.cpu().numpy().view(np.uint32), val.view(np.uint32)), (sc.shape[0], k)
+        for oi, ov in outs:
+            oi.fill_(-7)
+            ov.fill_(float("nan"))
+    # out_score may be NULL on this path too
+    sc, k = cases[0]
+    oi = torch.full((k,), -7, dtype=torch.int32, device="cuda")
+    api.fs_topk([api.TopkRequest(reqs[0].score, sc.shape[0], k, oi, None)])
+    torch.cuda.synchronize()
+    assert np.array_equal(oi.cpu().numpy(), oracle.topk(sc, k)[0])
+
+
 def test_repeat_calls_are_bit_identical_and_scratch_row_scores_work(api, oracle):
     import torch
     case = W.make_case(3, seed=4, scale=0.01, trees=25)
