@@ -4,9 +4,10 @@
 // The search that feeds the cost model is evolutionary (Section 2 of the paper: candidates are
 // generated, the model estimates them, the best are kept); between generations the survivors
 // of the cut keep their features and their scores, so only newly generated candidates need the
-// traversal kernels.  Two kernels: offsets (lengths of the kept programs, block scan, scores),
-// then rows (one workgroup per output tile copies 64 rows x all features; lane = output row, so
-// writes are whole 256-byte columns and reads follow the source programs' contiguous rows).
+// traversal kernels.  Three kernels: lengths of the kept programs and their scores, offsets
+// (block scan of the lengths), then rows (one workgroup per output tile copies 64 rows x all
+// features; lane = output row, so writes are whole 256-byte columns and reads follow the source
+// programs' contiguous rows).
 #include "fs_internal.h"
 
 namespace fs {
@@ -38,56 +39,104 @@ __device__ __forceinline__ int source_of(const GatherArgs &a, int p)
     return s;
 }
 
-// out_prog_off = exclusive scan of the kept programs' lengths; scores copied.  One workgroup.
+// Lengths of the kept programs into out_prog_off (-1 marks an index that is neither a program
+// nor the cut's padding), scores copied.  The kept indices are in score order, i.e. scattered
+// over the sources, so this part runs on many compute units.
+__global__ void __launch_bounds__(256)
+gather_lengths_kernel(GatherArgs a)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= a.n_keep)
+        return;
+    const int total_prog = a.first_prog[a.n_sources];
+    const int p = a.keep[i];
+    int len = 0;
+    float sc = -__builtin_inff();
+    if (p >= 0 && p < total_prog) {
+        const int s = source_of(a, p), q = p - a.first_prog[s];
+        len = a.prog_off[s][q + 1] - a.prog_off[s][q];
+        if (a.score[s])
+            sc = a.score[s][q];
+    } else if (p != -1) {
+        len = -1;                                    // -1 is the cut's padding: an empty program
+    }
+    a.out_prog_off[i] = len;
+    if (a.out_score)
+        a.out_score[i] = sc;
+}
+
+constexpr int kGatherPer = (FS_MAX_TOPK + kGatherThreads - 1) / kGatherThreads;   // kept programs per thread
+
+// out_prog_off: lengths -> their exclusive scan.  One workgroup; thread t holds entries
+// t, t + 1024, ... in registers (coalesced loads, all in flight at once).  Every run of 64
+// entries is scanned inside its wavefront with shuffles, the 16 x 16 run totals are scanned by
+// four wavefronts, and each entry's offset is its run's base plus its place in the run.
+constexpr int kGatherWaves = kGatherThreads / 64;
+constexpr int kGatherRuns = kGatherPer * kGatherWaves;       // 64-entry runs, in index order
+
+__device__ __forceinline__ long long wave_inclusive_scan(long long v, int lane)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const long long t = __shfl_up(v, off);
+        if (lane >= off)
+            v += t;
+    }
+    return v;
+}
+
 __global__ void __launch_bounds__(kGatherThreads)
 gather_offsets_kernel(GatherArgs a)
 {
-    __shared__ long long s_sum[kGatherThreads];
+    static_assert(kGatherRuns == 256, "the run totals are scanned by four wavefronts");
+    __shared__ long long s_run[kGatherRuns];         // totals of the runs, then their exclusive scan
+    __shared__ long long s_quarter[4];
     __shared__ int s_bad;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid == 0)
         s_bad = 0;
     __syncthreads();
-    const int per = (a.n_keep + kGatherThreads - 1) / kGatherThreads;
-    const int i0 = min(tid * per, a.n_keep), i1 = min(i0 + per, a.n_keep);
-    const int total_prog = a.first_prog[a.n_sources];
-    long long mine = 0;
-    for (int i = i0; i < i1; ++i) {
-        const int p = a.keep[i];
-        int len = 0;
-        float sc = -__builtin_inff();
-        if (p >= 0 && p < total_prog) {
-            const int s = source_of(a, p), q = p - a.first_prog[s];
-            len = a.prog_off[s][q + 1] - a.prog_off[s][q];
-            if (a.score[s])
-                sc = a.score[s][q];
-        } else if (p != -1) {
-            s_bad = 1;                               // -1 is the cut's padding: an empty program
-        }
-        if (a.out_score)
-            a.out_score[i] = sc;
-        mine += len;
+    int len[kGatherPer];
+#pragma unroll
+    for (int u = 0; u < kGatherPer; ++u) {
+        const int i = tid + u * kGatherThreads;
+        len[u] = i < a.n_keep ? a.out_prog_off[i] : 0;
     }
-    s_sum[tid] = mine;
+    bool bad = false;
+    long long incl[kGatherPer];
+#pragma unroll
+    for (int u = 0; u < kGatherPer; ++u) {
+        bad |= len[u] < 0;
+        len[u] = len[u] < 0 ? 0 : len[u];
+        incl[u] = wave_inclusive_scan((long long)len[u], lane);
+        if (lane == 63)
+            s_run[u * kGatherWaves + wave] = incl[u];    // run (u, wave) covers entries u*1024 + wave*64 ...
+    }
+    if (bad)
+        s_bad = 1;
     __syncthreads();
-    for (int off = 1; off < kGatherThreads; off <<= 1) {
-        long long v = 0;
-        if (tid >= off)
-            v = s_sum[tid - off];
-        __syncthreads();
-        s_sum[tid] += v;
-        __syncthreads();
+    long long run_incl = 0, run_total = 0;
+    if (tid < kGatherRuns) {
+        run_total = s_run[tid];
+        run_incl = wave_inclusive_scan(run_total, lane);
+        if (lane == 63)
+            s_quarter[wave] = run_incl;
     }
-    long long at = s_sum[tid] - mine;
-    const long long total = s_sum[kGatherThreads - 1];
+    __syncthreads();
+    if (tid < kGatherRuns) {
+        long long before = 0;
+        for (int w = 0; w < wave; ++w)
+            before += s_quarter[w];
+        s_run[tid] = before + run_incl - run_total;       // rows before this run
+    }
+    __syncthreads();
+    const long long total = s_quarter[0] + s_quarter[1] + s_quarter[2] + s_quarter[3];
     const bool fits = total <= a.out_row_capacity && total < ((long long)1 << 31);
-    for (int i = i0; i < i1; ++i) {
-        a.out_prog_off[i] = fits ? (int32_t)at : 0;
-        const int p = a.keep[i];
-        if (p >= 0 && p < total_prog) {
-            const int s = source_of(a, p), q = p - a.first_prog[s];
-            at += a.prog_off[s][q + 1] - a.prog_off[s][q];
-        }
+#pragma unroll
+    for (int u = 0; u < kGatherPer; ++u) {
+        const int i = tid + u * kGatherThreads;
+        if (i < a.n_keep)
+            a.out_prog_off[i] = fits ? (int32_t)(s_run[u * kGatherWaves + wave] + incl[u] - len[u]) : 0;
     }
     if (tid == 0) {
         a.out_prog_off[a.n_keep] = fits ? (int32_t)total : 0;
@@ -95,7 +144,11 @@ gather_offsets_kernel(GatherArgs a)
     }
 }
 
-// One workgroup per output tile: 64 rows x all features.
+// One workgroup per output tile: 64 rows x all features.  A thread's loads are issued in
+// batches before the stores that depend on them, so that the copy is not one round trip to
+// memory per column.
+constexpr int kGatherBatch = 8;
+
 __global__ void __launch_bounds__(256)
 gather_rows_kernel(GatherArgs a)
 {
@@ -106,9 +159,32 @@ gather_rows_kernel(GatherArgs a)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = r0 + lane;
     const int F = a.n_features;
-    const float *src = nullptr;
+    const float *__restrict__ src = nullptr;
     if (r < n_rows) {
-        int lo = 0, hi = a.n_keep - 1;              // the kept program that owns output row r
+        // The kept program that owns output row r: the last index whose offset is <= r.  Rows
+        // are spread about evenly over the programs, so the search starts from the proportional
+        // guess and gallops away from it; equal-length programs need two probes.
+        const int32_t *__restrict__ off = a.out_prog_off;
+        int lo = 0, hi = a.n_keep - 1;
+        const int g = min((int)(((int64_t)r * a.n_keep) / n_rows), hi);
+        if (off[g] <= r) {
+            lo = g;
+            int step = 1;
+            while (lo + step <= hi && off[lo + step] <= r) {
+                lo += step;
+                step <<= 1;
+            }
+            hi = min(hi, lo + step - 1);
+        } else {                                    // g >= 1: off[0] = 0 <= r
+            hi = g - 1;
+            int c = hi, step = 1;
+            while (c > 0 && off[c] > r) {
+                hi = c - 1;
+                c = max(c - step, 0);
+                step <<= 1;
+            }
+            lo = c;
+        }
         while (lo < hi) {
             const int mid = (lo + hi + 1) >> 1;
             if (a.out_prog_off[mid] <= r)
@@ -121,9 +197,21 @@ gather_rows_kernel(GatherArgs a)
         const int64_t sr = (int64_t)a.prog_off[s][q] + (r - a.out_prog_off[lo]);
         src = a.features[s] + (sr >> 6) * F * 64 + (sr & 63);
     }
-    float *dst = a.out_features + (int64_t)blockIdx.x * F * 64 + lane;
-    for (int j = wave; j < F; j += 4)
-        dst[(int64_t)j * 64] = src ? src[(int64_t)j * 64] : 0.0f;
+    float *__restrict__ dst = a.out_features + (int64_t)blockIdx.x * F * 64 + lane;
+    for (int j0 = wave; j0 < F; j0 += 4 * kGatherBatch) {
+        float v[kGatherBatch];
+#pragma unroll
+        for (int u = 0; u < kGatherBatch; ++u) {
+            const int j = j0 + 4 * u;
+            v[u] = (src && j < F) ? src[(int64_t)j * 64] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < kGatherBatch; ++u) {
+            const int j = j0 + 4 * u;
+            if (j < F)
+                dst[(int64_t)j * 64] = v[u];
+        }
+    }
 }
 
 }  // namespace fs
@@ -184,6 +272,8 @@ extern "C" int fs_gather_programs(int32_t n_features, int32_t n_sources, const f
     a.out_score = out_score;
     a.status = status;
     prof_start(kKernPack, stream);
+    if (n_keep > 0)
+        hipLaunchKernelGGL(gather_lengths_kernel, dim3((unsigned)((n_keep + 255) / 256)), dim3(256), 0, stream, a);
     hipLaunchKernelGGL(gather_offsets_kernel, dim3(1), dim3(kGatherThreads), 0, stream, a);
     const int64_t tiles = (out_row_capacity + 63) / 64;
     if (tiles > 0 && n_keep > 0)

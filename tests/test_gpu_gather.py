@@ -91,6 +91,35 @@ def test_gather_capacity_bad_indices_and_empty_requests(api, oracle):
         gather(api, devs, np.zeros(api.FS_MAX_TOPK + 1, np.int32), capacity=64)
 
 
+@pytest.mark.parametrize("order", ["long_first", "short_first", "random", "max_keep"])
+def test_gather_with_very_uneven_program_lengths(api, oracle, order):
+    """The row copy finds the owner of every output row by a search that starts from a
+    proportional guess: programs sorted by length (rows bunched at one end), many empty
+    programs and repeated indices put that guess far off on either side."""
+    fam = W.make_small_family(seed=75, n_programs=700, stmts=(0, 40), n_trees=2, depth=2, k=4)
+    devs = api.upload_case(W.Case("one", 0, [fam]))
+    lens = np.diff(fam.prog_off)
+    rng = np.random.default_rng(6)
+    if order == "long_first":
+        keep = np.argsort(-lens, kind="stable").astype(np.int32)
+    elif order == "short_first":
+        keep = np.argsort(lens, kind="stable").astype(np.int32)
+        keep[::5] = -1
+    elif order == "random":
+        keep = rng.integers(0, 700, 1500).astype(np.int32)            # repeats are allowed
+        keep[rng.integers(0, 1500, 400)] = -1
+    else:
+        short = np.flatnonzero(lens <= 2)
+        keep = short[rng.integers(0, short.shape[0], api.FS_MAX_TOPK)].astype(np.int32)
+        keep[-3:] = np.argsort(-lens)[:3]                              # the long ones last
+    ex, eoff, esc = oracle.gather_programs([(fam.features, fam.prog_off, None)], keep.tolist())
+    out_x, off, sc, status = gather(api, devs, keep, capacity=int(eoff[-1]), with_scores=False)
+    assert status == 0
+    assert np.array_equal(off, eoff)
+    got = api.unpack_colblock64(out_x, int(eoff[-1]), 164)
+    assert np.array_equal(got.view(np.uint32), ex.view(np.uint32))
+
+
 def test_generations_with_a_resident_population_match_rescoring_everything(api, oracle):
     """Three generations of: score only the new candidates, cut (old scores + new scores) to the
     population size, gather the survivors from (population, new) into the next population --
