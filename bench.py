@@ -267,7 +267,7 @@ def evolve_main(args, np, torch, api, W):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus %d is not supported "
+        print("bench.py: this library runs on one GPU only; --gpus %d is not supported "
               "(no collectives, no sharding in this library)" % args.gpus, file=sys.stderr)
         sys.exit(2)
     import numpy as np
