@@ -260,7 +260,7 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         if (!a.row_score)
             scratch_floats += (size_t)a.n_rows;
         if (a.model->rank_ok)                                // u16 rank tiles, in float units
-            scratch_floats += (size_t)((a.n_rows + 63) / 64) * 32 * (size_t)a.model->n_features + 4;
+            scratch_floats += (size_t)((a.n_rows + 63) / 64) * 32 * (size_t)rank_tile_cols(a.model->n_features) + 4;
         if ((a.model->rank_ok || a.model->lds_ok) && a.layout == FS_ROWMAJOR &&
             !rowmajor_in_kernel(a.model))                                         // re-tiled copy
             scratch_floats += (size_t)((a.n_rows + 63) / 64) * 64 * (size_t)a.model->n_features + 4;
@@ -353,7 +353,7 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
             const int64_t tiles = (a.n_rows + 63) / 64;
             scratch_pos = (scratch_pos + 3) & ~(size_t)3;            // 16-byte aligned tiles
             d.ranks = (uint16_t *)(ctx->scratch + scratch_pos);
-            scratch_pos += (size_t)tiles * 32 * (size_t)a.model->n_features;
+            scratch_pos += (size_t)tiles * 32 * (size_t)rank_tile_cols(a.model->n_features);
             const int len = 1 << a.model->cut_bits;
             int per_group = kBinTableBytes / 4 / len;
             if (per_group > a.model->n_features) per_group = a.model->n_features;

@@ -193,6 +193,13 @@ struct TopkPairDesc {
     int32_t la, lb, lo, k;
 };
 
+// u16 rank tiles keep the features of a row in pairs: features 2i and 2i+1 of row l share the
+// 32-bit word at i*256 + 4*l of the tile, so that lane l always reads from LDS bank l whichever
+// feature it asks for (with one u16 column after the other, two lanes would meet in every bank).
+// A tile therefore has an even number of columns.
+__host__ __device__ inline int rank_tile_cols(int n_features) { return (n_features + 1) & ~1; }
+__host__ __device__ inline uint32_t rank_feature_offset(int f) { return (uint32_t)(f >> 1) * 256u + (uint32_t)(f & 1) * 2u; }
+
 // ---- launchers (each returns FS_OK or records an error) ---------------------------------------
 int launch_traverse_global(const FamDesc *d_desc, int n_families, int total_blocks,
                            hipStream_t stream);

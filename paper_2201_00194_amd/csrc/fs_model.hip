@@ -148,7 +148,7 @@ size_t chunk_image_limit(int mode)
 
 // Rank-coded image of a model of perfect trees of one depth (see fs_rank.hip): per feature the
 // sorted distinct thresholds; per tree 2^(depth+1) words, word i = heap node i (1-based),
-// splits as rank << 16 | feature*128, leaves as value bits; plus the caller's node id per word.
+// splits as rank << 16 | offset of the feature in a rank tile, leaves as value bits; plus the caller's node id per word.
 void build_rank_format(fs_model *m, int n_features, int n_trees, int depth, const int32_t *tree_off,
                        const int32_t *sf, const float *thr, const int32_t *left,
                        const int32_t *right, const float *val, std::vector<uint32_t> *nodes,
@@ -206,7 +206,7 @@ void build_rank_format(fs_model *m, int n_features, int n_trees, int depth, cons
                     const std::vector<float> &v = per[(size_t)sf[o + n]];
                     rank = 1u + (uint32_t)(std::lower_bound(v.begin(), v.end(), th + 0.0f) - v.begin());
                 }
-                w = (rank << 16) | ((uint32_t)sf[o + n] * 128u);
+                w = (rank << 16) | rank_feature_offset(sf[o + n]);
             } else {
                 memcpy(&w, &val[o + n], 4);
             }
@@ -216,7 +216,7 @@ void build_rank_format(fs_model *m, int n_features, int n_trees, int depth, cons
     }
 
     // tiles per workgroup (must divide the wavefront count): most (tiles x trees per chunk)
-    const size_t tree_bytes = words * 4, tile_bytes = (size_t)n_features * 128;
+    const size_t tree_bytes = words * 4, tile_bytes = (size_t)rank_tile_cols(n_features) * 128;
     const size_t reg_limit = (size_t)kRankPrefetchRegs * 64 * kRankWaves * 16;
     int best_t = 0, best_per = 0, best_score = -1;
     int forced = 0;

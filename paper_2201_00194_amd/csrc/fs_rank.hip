@@ -106,7 +106,7 @@ rank_code_kernel(const FamDesc *__restrict__ descs, int n_families)
     }
     while (t < nt) {
         const int j0 = jg * kBinChains;
-        const int64_t base = ((int64_t)(t0 + t) * F + f0) * 64 + lane;
+        const int64_t base = (int64_t)(t0 + t) * rank_tile_cols(F) * 64 + 2 * lane;   // u16 units
         float x[kBinChains];
         uint32_t pos[kBinChains], tab[kBinChains];
 #pragma unroll
@@ -135,11 +135,26 @@ rank_code_kernel(const FamDesc *__restrict__ descs, int n_families)
             for (int k = 0; k < kBinChains; ++k)
                 pos[k] = 2u * pos[k] + ((c[k] <= x[k]) ? 1u : 0u);
         }
+        uint32_t r[kBinChains];
 #pragma unroll
-        for (int k = 0; k < kBinChains; ++k) {
-            const uint32_t r = (x[k] != x[k]) ? 65535u : (pos[k] - (uint32_t)len);
-            if (j0 + k < gf)
-                R[base + (int64_t)(j0 + k) * 64] = (uint16_t)r;
+        for (int k = 0; k < kBinChains; ++k)
+            r[k] = (x[k] != x[k]) ? 65535u : (pos[k] - (uint32_t)len);
+        if ((f0 & 1) == 0) {
+            // chains 2i and 2i+1 hold the two features of one word of the tile
+            auto R2 = FS_GLOBAL(uint32_t, d.ranks);
+#pragma unroll
+            for (int k = 0; k < kBinChains; k += 2) {
+                const int64_t at = base + (rank_feature_offset(f0 + j0 + k) >> 1);   // even
+                if (j0 + k + 1 < gf)
+                    R2[at >> 1] = r[k] | (r[k + 1] << 16);
+                else if (j0 + k < gf)
+                    R[at] = (uint16_t)r[k];
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < kBinChains; ++k)
+                if (j0 + k < gf)
+                    R[base + (rank_feature_offset(f0 + j0 + k) >> 1)] = (uint16_t)r[k];
         }
         t = tn;
         jg = jn;
@@ -177,8 +192,9 @@ int launch_rank_code(const FamDesc *d_desc, int n_families, int total_blocks, hi
 //                                               2^(depth+1) words: [unused][splits in heap
 //                                               order, 1-based][leaf values]
 //           [tile0 - trees*T*256, tile0)        leaf values parked per [tree][tile][lane]
-//           [tile0 + t*F*128, ...)              tile t: column j at j*128, row l at +2*l
-// A split word is rank(thr) << 16 | feature*128.
+//           [tile0 + t*Fc*128, ...)             tile t: features 2i, 2i+1 of row l in the word at
+//                                               i*256 + 4*l (Fc = F rounded up to even)
+// A split word is rank(thr) << 16 | offset of the feature in a tile (i*256 + 2*(f & 1)).
 
 // K trees at once for this lane's row.  base[k] = LDS address of tree k; the 1-based heap
 // index i lives at A = base + 4*i, and the step i' = 2i + c is taken on the address itself:
@@ -289,9 +305,10 @@ traverse_rank_kernel(const FamDesc *__restrict__ descs, int n_families)
     const int tiles_here = min(T, n_tiles - tile_first);
     const bool active = my_tile < tiles_here;
     const int F = d.n_features;
-    const uint32_t tile_bytes = (uint32_t)F * 128u;
+    const int Fc = rank_tile_cols(F);
+    const uint32_t tile_bytes = (uint32_t)Fc * 128u;
     const uint32_t tile0 = (uint32_t)d.rk_tile0;
-    const uint32_t lane_base = tile0 + (uint32_t)my_tile * tile_bytes + 2u * (uint32_t)lane;
+    const uint32_t lane_base = tile0 + (uint32_t)my_tile * tile_bytes + 4u * (uint32_t)lane;
     const uint32_t tree_bytes = (uint32_t)d.rk_tree_bytes;
     const int per_chunk = d.rk_trees_per_chunk;
     const int n_trees = d.n_trees;
@@ -311,8 +328,8 @@ traverse_rank_kernel(const FamDesc *__restrict__ descs, int n_families)
     }
     // ---- rank tiles: consecutive tiles are one contiguous run ----
     {
-        auto src = FS_GLOBAL(const u32x4, d.ranks + (int64_t)tile_first * F * 64);
-        const int per_tile = F * 8;                        // 16-byte pieces per tile
+        auto src = FS_GLOBAL(const u32x4, d.ranks + (int64_t)tile_first * Fc * 64);
+        const int per_tile = Fc * 8;                       // 16-byte pieces per tile
         const int n16 = tiles_here * per_tile;
         for (int base = tid; base < n16; base += kRankTileBatch * kRankThreads) {
             u32x4 t4[kRankTileBatch];
