@@ -59,6 +59,7 @@ struct TrainDesc {
     int32_t *best_cut;
     long long *best_GL, *best_HL;
     int32_t *counters;         // [0] next node id of the tree in work, [1] trees, [2] nodes
+    unsigned long long *abs_q; // sum over the rows of |gradient| (fixed point) of the round in work
     int32_t *m_tree_off, *m_feat, *m_left, *m_right;
     float *m_thr, *m_val;
     int64_t r_pad;
@@ -170,8 +171,10 @@ train_begin_tree_kernel(const TrainDesc *__restrict__ descs)
         d.h_id[i] = 0;
         d.h_val[i] = 0.0f;
     }
-    if (threadIdx.x == 0)
+    if (threadIdx.x == 0) {
         d.counters[0] = 1;
+        *d.abs_q = 0ull;
+    }
 }
 
 __device__ __forceinline__ int quantize(float g, float grad_scale)
@@ -189,6 +192,7 @@ train_grad_kernel(const TrainDesc *__restrict__ descs, float grad_scale, int wit
     const TrainDesc &d = descs[blockIdx.y];
     const int p = blockIdx.x * blockDim.x + threadIdx.x;
     long long G = 0, H = 0;
+    unsigned long long A = 0;                        // |gradient| x rows: bounds every histogram sum
     if (p < d.n_programs) {
         const int b = d.prog_off[p], e = d.prog_off[p + 1];
         float s = 0.0f;
@@ -204,6 +208,7 @@ train_grad_kernel(const TrainDesc *__restrict__ descs, float grad_scale, int wit
             }
             G = (long long)q * len;
             H = (long long)len * len;
+            A = (unsigned long long)(G < 0 ? -G : G);
         }
     }
     if (!with_grad)
@@ -212,10 +217,12 @@ train_grad_kernel(const TrainDesc *__restrict__ descs, float grad_scale, int wit
     for (int off = 32; off > 0; off >>= 1) {
         G += __shfl_down(G, off);
         H += __shfl_down(H, off);
+        A += __shfl_down(A, off);
     }
     if ((threadIdx.x & 63) == 0 && H != 0) {
         atomicAdd((unsigned long long *)&d.h_G[0], (unsigned long long)G);
         atomicAdd((unsigned long long *)&d.h_H[0], (unsigned long long)H);
+        atomicAdd(d.abs_q, A);
     }
 }
 
@@ -318,45 +325,34 @@ __device__ __forceinline__ void wave_best_cut(const TrainDesc &d, const Params &
 }
 
 // Histograms of one level.  A workgroup takes a slab of rows, four consecutive features (one
-// 32-bit word of bins per row) and up to kHistSlots nodes of the level, and keeps their (G, H)
+// 32-bit word of bins per row) and a run of nodes of the level, and keeps their (G, H)
 // histograms in LDS.  blockIdx = (slab, feature group, trainer * passes + pass); a pass covers
-// kHistSlots consecutive nodes.  With one slab per family the workgroup holds the complete
-// histograms and searches the cuts itself; with more slabs the partial histograms are added
-// to the global buffer (which is all zero: the split kernel clears what it reads) and
-// train_split_kernel does the search.
-constexpr int kHistSlots = 8;
+// consecutive nodes.  With one slab per family the workgroup holds the complete histograms and
+// searches the cuts itself; with more slabs the partial histograms are added to the global
+// buffer (which is all zero: the split kernel clears what it reads) and train_split_kernel
+// does the search.
+//
+// Two forms of a bin in LDS.  Packed: one 64-bit word G * 2^hb + H, fed by one atomic per
+// (row, feature); hb bits hold any curvature sum of the slab (the host knows rows x longest
+// program) and the rest holds G as long as the sum of |gradient| over the trainer's rows,
+// which train_grad_kernel leaves in abs_q, stays below 2^(63-hb).  Wide: G and H in 64 bits
+// each, always safe; a workgroup launched for the packed form falls back to it, its nodes in
+// two halves, when the gradients of its trainer are too large.  Both are exact integer sums.
+constexpr int kHistSlotsWide = 8;       // 8 nodes x 4 features x 256 bins x 16 B = 128 KB
+constexpr int kHistSlotsPacked = 16;    // 16 nodes x 4 features x 256 bins x 8 B = 128 KB
 
-// HT: type of the curvature sums in LDS.  A bin can hold up to (rows of the slab) x (rows of the
-// longest program); the host picks 64-bit sums when that may pass 2^32.
-template <class HT>
-__global__ void __launch_bounds__(kHistThreads)
-train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, int rows_per_slab,
-                  int n_slabs, Params prm)
+// One run of `slots` nodes, the first being number `abs0` of its level (heap index node0).
+template <bool PACKED>
+__device__ __forceinline__ void hist_run(const TrainDesc &d, const Params &prm,
+                                         unsigned long long *lds_hist, int node0, int abs0, int slots,
+                                         int row0, int row1, int f0, int nf, const int (&hot)[4],
+                                         const uint32_t *__restrict__ words, int n_slabs, int hb)
 {
-    extern __shared__ unsigned long long lds_hist[];            // G: [pairs][256] u64, then H: HT
-    const TrainDesc &d = descs[blockIdx.z / passes];
-    const int pass = blockIdx.z % passes;
-    const int row0 = blockIdx.x * rows_per_slab;
-    const int f0 = blockIdx.y * 4;
-    if (row0 >= d.n_rows || f0 >= d.n_features)
-        return;
-    const int row1 = min(row0 + rows_per_slab, d.n_rows);
-    const int nf = min(4, d.n_features - f0);
-    const int n_slots = 1 << level;
-    const int slots = min(kHistSlots, n_slots);
-    const int node0 = n_slots - 1 + pass * slots;               // heap index of slot 0
     const int pairs = slots * 4;
-    HT *lds_h = (HT *)(lds_hist + pairs * kBins);
-    for (int i = threadIdx.x; i < pairs * kBins; i += kHistThreads) {
+    unsigned long long *lds_h = lds_hist + pairs * kBins;       // wide form only
+    for (int i = threadIdx.x; i < pairs * kBins * (PACKED ? 1 : 2); i += kHistThreads)
         lds_hist[i] = 0ull;
-        lds_h[i] = (HT)0;
-    }
-    int hot[4];
-#pragma unroll
-    for (int fi = 0; fi < 4; ++fi)
-        hot[fi] = fi < nf ? d.hot_bin[f0 + fi] : 256;           // 256: no bin, nothing is skipped
     __syncthreads();
-    const uint32_t *__restrict__ words = (const uint32_t *)d.bins + (int64_t)blockIdx.y * d.r_pad;
     constexpr int kUnroll = 8;
     for (int base = row0 + threadIdx.x; base < row1; base += kHistThreads * kUnroll) {
         int slot[kUnroll];
@@ -373,18 +369,35 @@ train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, in
         for (int u = 0; u < kUnroll; ++u) {
             if (base + u * kHistThreads >= row1 || (unsigned)slot[u] >= (unsigned)slots)
                 continue;
+            const unsigned long long both =
+                (unsigned long long)((long long)qh[u].x * ((long long)1 << hb) + (long long)qh[u].y);
 #pragma unroll
             for (int fi = 0; fi < 4; ++fi) {
                 const int b = (w[u] >> (8 * fi)) & 255;
                 if (fi >= nf || b == hot[fi])
                     continue;                                    // rebuilt from the node's total
                 const int at = (slot[u] * 4 + fi) * kBins + b;
-                atomicAdd(&lds_hist[at], (unsigned long long)(long long)qh[u].x);
-                atomicAdd(&lds_h[at], (HT)qh[u].y);
+                if (PACKED) {
+                    atomicAdd(&lds_hist[at], both);
+                } else {
+                    atomicAdd(&lds_hist[at], (unsigned long long)(long long)qh[u].x);
+                    atomicAdd(&lds_h[at], (unsigned long long)qh[u].y);
+                }
             }
         }
     }
     __syncthreads();
+    const long long h_mask = ((long long)1 << hb) - 1;
+    auto bin_at = [&](int i, long long &g, long long &h) {
+        if (PACKED) {
+            const long long v = (long long)lds_hist[i];
+            h = v & h_mask;
+            g = (v - h) >> hb;                                   // v - h is a multiple of 2^hb
+        } else {
+            g = (long long)lds_hist[i];
+            h = (long long)lds_h[i];
+        }
+    };
     if (n_slabs == 1) {
         // The whole histogram of these nodes and features is here: search the cuts right away
         // (one wavefront per (node, feature)); nothing goes through the global buffer.
@@ -396,23 +409,60 @@ train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, in
                 continue;
             long long g[4], h[4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                g[k] = (long long)lds_hist[pair * kBins + 4 * lane + k];
-                h[k] = (long long)lds_h[pair * kBins + 4 * lane + k];
-            }
-            wave_best_cut(d, prm, node, f0 + fi, (pass * slots + slot) * d.n_features + f0 + fi, lane, g, h);
+            for (int k = 0; k < 4; ++k)
+                bin_at(pair * kBins + 4 * lane + k, g[k], h[k]);
+            wave_best_cut(d, prm, node, f0 + fi, (abs0 + slot) * d.n_features + f0 + fi, lane, g, h);
         }
-        return;
+    } else {
+        for (int i = threadIdx.x; i < pairs * kBins; i += kHistThreads) {
+            const int pair = i / kBins, b = i - pair * kBins;
+            const int slot = pair >> 2, fi = pair & 3;
+            long long g, h;
+            bin_at(i, g, h);
+            if (fi >= nf || h == 0)
+                continue;
+            const int64_t at = (((int64_t)(abs0 + slot) * d.n_features + (f0 + fi)) * kBins + b) * 2;
+            atomicAdd(&d.hist[at], (unsigned long long)g);
+            atomicAdd(&d.hist[at + 1], (unsigned long long)h);
+        }
     }
-    for (int i = threadIdx.x; i < pairs * kBins; i += kHistThreads) {
-        const int pair = i / kBins, b = i - pair * kBins;
-        const int slot = pair >> 2, fi = pair & 3;
-        const unsigned long long h = (unsigned long long)lds_h[i];
-        if (fi >= nf || h == 0ull)
-            continue;
-        const int64_t at = (((int64_t)(pass * slots + slot) * d.n_features + (f0 + fi)) * kBins + b) * 2;
-        atomicAdd(&d.hist[at], lds_hist[i]);
-        atomicAdd(&d.hist[at + 1], h);
+    __syncthreads();                                             // LDS may be reused by the next run
+}
+
+template <bool PACKED>
+__global__ void __launch_bounds__(kHistThreads)
+train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, int rows_per_slab,
+                  int n_slabs, int hb, Params prm)
+{
+    extern __shared__ unsigned long long lds_hist[];
+    const TrainDesc &d = descs[blockIdx.z / passes];
+    const int pass = blockIdx.z % passes;
+    const int row0 = blockIdx.x * rows_per_slab;
+    const int f0 = blockIdx.y * 4;
+    if (row0 >= d.n_rows || f0 >= d.n_features)
+        return;
+    const int row1 = min(row0 + rows_per_slab, d.n_rows);
+    const int nf = min(4, d.n_features - f0);
+    const int n_slots = 1 << level;
+    const int slots = min(PACKED ? kHistSlotsPacked : kHistSlotsWide, n_slots);
+    const int abs0 = pass * slots;                               // first node of the pass, within the level
+    const int node0 = n_slots - 1 + abs0;                        // its heap index
+    int hot[4];
+#pragma unroll
+    for (int fi = 0; fi < 4; ++fi)
+        hot[fi] = fi < nf ? d.hot_bin[f0 + fi] : 256;           // 256: no bin, nothing is skipped
+    const uint32_t *__restrict__ words = (const uint32_t *)d.bins + (int64_t)blockIdx.y * d.r_pad;
+    if (PACKED) {
+        if (*d.abs_q < (1ull << (63 - hb))) {
+            hist_run<true>(d, prm, lds_hist, node0, abs0, slots, row0, row1, f0, nf, hot, words, n_slabs, hb);
+        } else {
+            const int half = slots > 1 ? slots / 2 : 1;          // the wide form takes twice the LDS per node
+            for (int s = 0; s < slots; s += half)
+                hist_run<false>(d, prm, lds_hist, node0 + s, abs0 + s, half, row0, row1, f0, nf, hot, words,
+                                n_slabs, 0);
+        }
+    } else {
+        hist_run<false>(d, prm, lds_hist, node0, abs0, slots, row0, row1, f0, nf, hot, words, n_slabs, 0);
     }
 }
 
@@ -765,6 +815,7 @@ extern "C" int fs_trainer_create(fs_trainer **out, int32_t n_features, const flo
     TRY(dev_alloc(t, &h.best_GL, (size_t)hist_slots * n_features));
     TRY(dev_alloc(t, &h.best_HL, (size_t)hist_slots * n_features));
     TRY(dev_alloc(t, &h.counters, (size_t)4));
+    TRY(dev_alloc(t, &h.abs_q, (size_t)1));
     TRY(dev_alloc(t, &h.m_tree_off, (size_t)max_trees + 1));
     TRY(dev_alloc(t, &h.m_feat, (size_t)node_cap));
     TRY(dev_alloc(t, &h.m_left, (size_t)node_cap));
@@ -976,21 +1027,31 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
         int dev = 0;
         FS_HIP(hipGetDevice(&dev));
         if (!hist_configured[dev]) {
-            FS_HIP(hipFuncSetAttribute((const void *)train_hist_kernel<unsigned int>,
+            FS_HIP(hipFuncSetAttribute((const void *)train_hist_kernel<true>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kHistSlots * 4 * kBins * 12));
-            FS_HIP(hipFuncSetAttribute((const void *)train_hist_kernel<unsigned long long>,
+                                       kHistSlotsPacked * 4 * kBins * 8));
+            FS_HIP(hipFuncSetAttribute((const void *)train_hist_kernel<false>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kHistSlots * 4 * kBins * 16));
+                                       kHistSlotsWide * 4 * kBins * 16));
             hist_configured[dev] = true;
         }
     }
     const unsigned nt = (unsigned)n_trainers;
     const unsigned row_blocks = (unsigned)((max_rows + 255) / 256);
     const int rows_per_slab = (((max_rows + n_slabs - 1) / n_slabs) + 63) & ~63;
-    // 32-bit curvature sums in LDS unless a bin of a slab could pass 2^32
-    const bool wide_h = (long long)max_len * (long long)(rows_per_slab < max_rows ? rows_per_slab : max_rows) >=
-                        ((long long)1 << 32);
+    // Bits that hold any curvature sum of a slab (rows x longest program bounds it).  The packed
+    // form of the histograms needs room for the gradient sums beside them; beyond 31 bits the
+    // wide form is launched right away.
+    int hb = 1;
+    {
+        const long long bound = (long long)max_len * (long long)(rows_per_slab < max_rows ? rows_per_slab : max_rows);
+        while (hb < 63 && ((long long)1 << hb) <= bound)
+            ++hb;
+    }
+    bool packed = hb <= 31;
+    if (const char *e = getenv("FS_TUNE_TRAIN_PACKED"))          // tuning / test aid: 0 = wide form only
+        if (atoi(e) == 0)
+            packed = false;
     for (int round = 0; round < n_rounds; ++round) {
         prof_start(kKernTrainOther, stream);
         hipLaunchKernelGGL(train_begin_tree_kernel, dim3(nt), dim3(512), 0, stream, d);
@@ -999,18 +1060,23 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
         prof_stop(stream);
         for (int level = 0; level < prm.max_depth; ++level) {
             const int n_slots = 1 << level;
-            const int slots = n_slots < kHistSlots ? n_slots : kHistSlots;
+            const int per_pass = packed ? kHistSlotsPacked : kHistSlotsWide;
+            const int slots = n_slots < per_pass ? n_slots : per_pass;
             const int passes = n_slots / slots;
             const dim3 hgrid((unsigned)n_slabs, (unsigned)((max_feat + 3) / 4), nt * passes);
             prof_start(kKernTrainHist, stream);
-            if (wide_h)
-                hipLaunchKernelGGL(train_hist_kernel<unsigned long long>, hgrid, dim3(kHistThreads),
+            if (packed) {
+                // a lone node still needs the 16 KB of its wide form for the fall-back
+                size_t lds = (size_t)slots * 4 * kBins * 8;
+                if (lds < (size_t)4 * kBins * 16)
+                    lds = (size_t)4 * kBins * 16;
+                hipLaunchKernelGGL(train_hist_kernel<true>, hgrid, dim3(kHistThreads), lds, stream, d, level,
+                                   passes, rows_per_slab, n_slabs, hb, prm);
+            } else {
+                hipLaunchKernelGGL(train_hist_kernel<false>, hgrid, dim3(kHistThreads),
                                    (size_t)slots * 4 * kBins * 16, stream, d, level, passes, rows_per_slab,
-                                   n_slabs, prm);
-            else
-                hipLaunchKernelGGL(train_hist_kernel<unsigned int>, hgrid, dim3(kHistThreads),
-                                   (size_t)slots * 4 * kBins * 12, stream, d, level, passes, rows_per_slab,
-                                   n_slabs, prm);
+                                   n_slabs, 0, prm);
+            }
             prof_stop(stream);
             prof_start(kKernTrainSplit, stream);
             if (n_slabs > 1)

@@ -195,3 +195,30 @@ def test_many_tied_and_near_tied_cuts(api, T):
     big = W.TrainSet(X * np.float32(3e4), off, (y * np.float32(1000)).astype(np.float32),
                      *W.draw_cuts(X * np.float32(3e4), 255))
     check(api, T, big, rounds=3, max_depth=4, eta=0.5, lam=0.0, grad_scale=float(1 << 20))
+
+
+def test_histogram_forms_packed_wide_and_fallback(api, T, monkeypatch):
+    """The histogram kernel keeps (G, H) of a bin packed in one 64-bit word while the round's
+    gradients leave room for it, and falls back inside the kernel to separate 64-bit sums when
+    they do not; FS_TUNE_TRAIN_PACKED=0 launches the separate sums outright.  All three must
+    give the oracle's trees.  Huge targets make the fixed-point gradients hit their clamp
+    (+-2^31), so that their sum over the rows passes what the packed form can hold."""
+    ts = W.make_train_set(41, 2500, stmts=(1, 40), n_features=30, max_cuts=120)
+    assert 40_000 < ts.n_rows <= 65_536
+    kw = dict(rounds=3, max_depth=6, eta=0.5, lam=1.0)
+    check(api, T, ts, **kw)                                          # packed
+    monkeypatch.setenv("FS_TUNE_TRAIN_PACKED", "0")
+    check(api, T, ts, **kw)                                          # wide
+    monkeypatch.delenv("FS_TUNE_TRAIN_PACKED")
+    huge = W.TrainSet(ts.features, ts.prog_off, (ts.target * np.float32(1e7)).astype(np.float32),
+                      ts.cut_off, ts.cuts)
+    # the packed form has 63 - 21 bits for gradient sums here (rows x longest program < 2^21);
+    # the clamped gradients add up to about rows x 2^31
+    assert np.sum(np.abs(huge.target) > 4096) > 0.9 * huge.target.shape[0]
+    assert 0.9 * huge.n_rows * float(1 << 31) > 2.0 ** 44
+    check(api, T, huge, rounds=2, max_depth=5, eta=0.5, lam=1.0)      # fallback in the first round
+    check(api, T, huge, rounds=2, max_depth=0, eta=0.5, lam=1.0)
+    monkeypatch.setenv("FS_TUNE_TRAIN_SLAB_ROWS", "20000")
+    check(api, T, ts, **kw)                                          # packed, several slabs
+    check(api, T, huge, rounds=2, max_depth=5, eta=0.5, lam=1.0)      # fallback, several slabs
+    monkeypatch.delenv("FS_TUNE_TRAIN_SLAB_ROWS")
