@@ -35,6 +35,15 @@ constexpr int kBins = FS_TRAIN_MAX_CUTS + 1;                      // 256
 constexpr int kHistThreads = 1024;
 constexpr int kHistRowsPerSlab = 65536;
 
+// Deep trees: from this level on a histogram pass covers a small share of the nodes, and
+// streaming all rows for every pass is what the time goes into.  Before that level's histograms
+// the rows are regrouped once by their node of the level; the rows of a node's descendants stay
+// inside its segment, so a pass over some nodes of a deeper level reads only the segments of
+// their ancestors on this level.
+constexpr int kSortLevel = 5;
+constexpr int kSortSegs = 1 << kSortLevel;             // 32 nodes, heap indices 31..62
+constexpr int kSortMinDepth = 7;                       // worth it when at least two levels use it
+
 // heap node states
 enum { kAbsent = 0, kOpen = 1, kInternal = 2, kLeaf = 3 };
 
@@ -60,6 +69,14 @@ struct TrainDesc {
     long long *best_GL, *best_HL;
     int32_t *counters;         // [0] next node id of the tree in work, [1] trees, [2] nodes
     unsigned long long *abs_q; // sum over the rows of |gradient| (fixed point) of the round in work
+    // Rows regrouped by their node of level kSortLevel (deep trees only, see train_seg_* below):
+    uint8_t *s_bins;           // bins in that order, same layout as `bins`
+    int2 *s_qh;
+    int32_t *s_rowid;          // original row of a regrouped position
+    uint16_t *s_node;          // node that holds it (kept up to date below kSortLevel)
+    int32_t *s_dest;           // scratch: regrouped position of an original row, -1 if it stayed behind
+    int32_t *seg_start;        // kSortSegs + 1: first position of every node of level kSortLevel
+    int32_t *seg_cursor;       // kSortSegs: counts, then fill positions
     int32_t *m_tree_off, *m_feat, *m_left, *m_right;
     float *m_thr, *m_val;
     int64_t r_pad;
@@ -175,6 +192,8 @@ train_begin_tree_kernel(const TrainDesc *__restrict__ descs)
         d.counters[0] = 1;
         *d.abs_q = 0ull;
     }
+    if (d.seg_cursor && threadIdx.x < kSortSegs)
+        d.seg_cursor[threadIdx.x] = 0;
 }
 
 __device__ __forceinline__ int quantize(float g, float grad_scale)
@@ -252,32 +271,27 @@ __device__ __forceinline__ long long shfl_up_ll(long long v, int off) { return _
 
 // Best cut of feature f for the open node `node`, by one wavefront: lane l holds bins 4l..4l+3
 // (g, h; the feature's most frequent bin holds 0 and is rebuilt here from the node's totals)
-// and answers for the cuts 4l+1..4l+4.  Lane 0 writes the result for `pair` = slot * F + f.
+// and forms the left sums of the cuts 4l+1..4l+4.  Lane 0 writes the result for
+// `pair` = slot * F + f.
+//
+// A cut behind an empty bin splits the node exactly as the cut before it does: same gain, and
+// coming later it never wins.  (A row's curvature is at least 1, so a bin is empty exactly when
+// its H is 0.)  Deep in a tree a node holds fewer rows than a feature has bins and most cuts
+// drop out this way; when at most 64 are left they are handed out one per lane through
+// `scratch` (this wavefront's own kCutScratchBytes of LDS), so that the wavefront pays for one
+// round of double-precision divisions instead of four.  Measured: the cut search is two thirds
+// of the histogram kernel's time at depth 10.
+constexpr int kCutScratchBytes = 64 * (8 + 8 + 4);
+
 __device__ __forceinline__ void wave_best_cut(const TrainDesc &d, const Params &prm, int node, int f,
-                                              int pair, int lane, long long (&g)[4], long long (&h)[4])
+                                              int pair, int lane, long long (&g)[4], long long (&h)[4],
+                                              unsigned char *scratch)
 {
     const long long G = d.h_G[node], H = d.h_H[node];
-    long long og = g[0] + g[1] + g[2] + g[3], oh = h[0] + h[1] + h[2] + h[3];
-    for (int off = 32; off > 0; off >>= 1) {
-        og += __shfl_xor(og, off);
-        oh += __shfl_xor(oh, off);
-    }
     const int hot = d.hot_bin[f];
-    if ((hot >> 2) == lane) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if ((hot & 3) == k) {
-                g[k] = G - og;
-                h[k] = H - oh;
-            }
-    }
-    // inclusive prefix sums over the 256 bins
-#pragma unroll
-    for (int k = 1; k < 4; ++k) {
-        g[k] += g[k - 1];
-        h[k] += h[k - 1];
-    }
-    long long pg = g[3], ph = h[3];                              // this lane's total -> scan
+    // inclusive prefix sums over the 256 bins, the hot bin still at 0
+    long long pg = g[0] + g[1] + g[2] + g[3], ph = h[0] + h[1] + h[2] + h[3];   // this lane's total -> scan
+    const long long lane_g = pg, lane_h = ph;
     for (int off = 1; off < 64; off <<= 1) {
         const long long ug = shfl_up_ll(pg, off), uh = shfl_up_ll(ph, off);
         if (lane >= off) {
@@ -285,38 +299,110 @@ __device__ __forceinline__ void wave_best_cut(const TrainDesc &d, const Params &
             ph += uh;
         }
     }
-    const long long before_g = pg - g[3], before_h = ph - h[3];
+    // what the counted bins lack of the node's totals sits in the hot bin
+    const long long hot_g = G - __shfl(pg, 63), hot_h = H - __shfl(ph, 63);
+    long long before_g = pg - lane_g, before_h = ph - lane_h;
+    if ((hot >> 2) < lane) {
+        before_g += hot_g;
+        before_h += hot_h;
+    }
+    if ((hot >> 2) == lane) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if ((hot & 3) == k) {
+                g[k] = hot_g;
+                h[k] = hot_h;
+            }
+    }
+    bool filled[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        filled[k] = h[k] != 0;
+#pragma unroll
+    for (int k = 1; k < 4; ++k) {
+        g[k] += g[k - 1];
+        h[k] += h[k - 1];
+    }
     const int m = d.cut_off[f + 1] - d.cut_off[f];
     const double t3 = parent_term(G, H, prm.inv_scale, prm.lambda);
+    // cut 4l+k+1 (left = bins 0..4l+k) is worth evaluating if it is in range, follows a
+    // non-empty bin and leaves enough curvature on both sides
+    bool cand[4];
+    unsigned long long vote[4];
+    int n_cand = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const long long HL = before_h + h[k];
+        cand[k] = 4 * lane + k + 1 <= m && filled[k] && HL >= prm.mcw && H - HL >= prm.mcw;
+        vote[k] = __ballot(cand[k]);
+        n_cand += __popcll(vote[k]);
+    }
     int cut = 0;
     double gain = 0.0;
     long long bGL = 0, bHL = 0;
+    if (n_cand <= 64) {
+        // one candidate per lane (which lane takes which does not matter: ties are settled on
+        // the cut number below)
+        long long *s_GL = (long long *)scratch;
+        long long *s_HL = s_GL + 64;
+        int *s_cut = (int *)(s_HL + 64);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        int first = 0;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {                                // cut 4l+k+1: left = bins 0..4l+k
-        const long long GL = before_g + g[k], HL = before_h + h[k];
-        const int j = 4 * lane + k + 1;
-        if (j <= m && HL >= prm.mcw && H - HL >= prm.mcw) {
-            const double gn = split_gain(GL, HL, G, H, prm.inv_scale, prm.lambda, t3);
-            if (cut == 0 || gn > gain) {                         // ascending cuts: first of equals stays
-                gain = gn;
-                cut = j;
-                bGL = GL;
-                bHL = HL;
+        for (int k = 0; k < 4; ++k) {
+            if (cand[k]) {
+                const int at = first + __popcll(vote[k] & below);
+                s_GL[at] = before_g + g[k];
+                s_HL[at] = before_h + h[k];
+                s_cut[at] = 4 * lane + k + 1;
+            }
+            first += __popcll(vote[k]);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (lane < n_cand) {
+            bGL = s_GL[lane];
+            bHL = s_HL[lane];
+            cut = s_cut[lane];
+            gain = split_gain(bGL, bHL, G, H, prm.inv_scale, prm.lambda, t3);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();                         // the next search of this wavefront reuses the scratch
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (cand[k]) {
+                const long long GL = before_g + g[k], HL = before_h + h[k];
+                const double gn = split_gain(GL, HL, G, H, prm.inv_scale, prm.lambda, t3);
+                if (cut == 0 || gn > gain) {                     // ascending cuts: first of equals stays
+                    gain = gn;
+                    cut = 4 * lane + k + 1;
+                    bGL = GL;
+                    bHL = HL;
+                }
             }
         }
     }
+    double best = gain;
+    int best_cut = cut;
     for (int off = 32; off > 0; off >>= 1) {                     // largest gain, lowest cut on ties
-        const double og2 = __shfl_xor(gain, off);
-        const int oc = __shfl_xor(cut, off);
-        const long long ogl = __shfl_xor(bGL, off), ohl = __shfl_xor(bHL, off);
-        if (oc != 0 && (cut == 0 || og2 > gain || (og2 == gain && oc < cut))) {
-            gain = og2;
-            cut = oc;
-            bGL = ogl;
-            bHL = ohl;
+        const double og2 = __shfl_xor(best, off);
+        const int oc = __shfl_xor(best_cut, off);
+        if (oc != 0 && (best_cut == 0 || og2 > best || (og2 == best && oc < best_cut))) {
+            best = og2;
+            best_cut = oc;
         }
     }
-    if (lane == 0) {
+    if (best_cut == 0) {
+        if (lane == 0) {
+            d.best_gain[pair] = 0.0;
+            d.best_cut[pair] = 0;
+            d.best_GL[pair] = 0;
+            d.best_HL[pair] = 0;
+        }
+    } else if (cut == best_cut) {                                // exactly one lane holds the winner
         d.best_gain[pair] = gain;
         d.best_cut[pair] = cut;
         d.best_GL[pair] = bGL;
@@ -340,13 +426,17 @@ __device__ __forceinline__ void wave_best_cut(const TrainDesc &d, const Params &
 // two halves, when the gradients of its trainer are too large.  Both are exact integer sums.
 constexpr int kHistSlotsWide = 8;       // 8 nodes x 4 features x 256 bins x 16 B = 128 KB
 constexpr int kHistSlotsPacked = 16;    // 16 nodes x 4 features x 256 bins x 8 B = 128 KB
+constexpr int kHistCutScratch = (kHistThreads / 64) * kCutScratchBytes;   // 20 KB in front of them
 
 // One run of `slots` nodes, the first being number `abs0` of its level (heap index node0).
 template <bool PACKED>
 __device__ __forceinline__ void hist_run(const TrainDesc &d, const Params &prm,
                                          unsigned long long *lds_hist, int node0, int abs0, int slots,
                                          int row0, int row1, int f0, int nf, const int (&hot)[4],
-                                         const uint32_t *__restrict__ words, int n_slabs, int hb)
+                                         const uint32_t *__restrict__ words,
+                                         const uint16_t *__restrict__ node_of,
+                                         const int2 *__restrict__ qh_of, int n_slabs, int hb,
+                                         unsigned char *cut_scratch)
 {
     const int pairs = slots * 4;
     unsigned long long *lds_h = lds_hist + pairs * kBins;       // wide form only
@@ -361,9 +451,9 @@ __device__ __forceinline__ void hist_run(const TrainDesc &d, const Params &prm,
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {                      // loads first
             const int r = min(base + u * kHistThreads, row1 - 1);
-            slot[u] = (int)d.node_of_row[r] - node0;
+            slot[u] = (int)node_of[r] - node0;
             w[u] = words[r];
-            qh[u] = d.qh[r];
+            qh[u] = qh_of[r];
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -411,7 +501,8 @@ __device__ __forceinline__ void hist_run(const TrainDesc &d, const Params &prm,
 #pragma unroll
             for (int k = 0; k < 4; ++k)
                 bin_at(pair * kBins + 4 * lane + k, g[k], h[k]);
-            wave_best_cut(d, prm, node, f0 + fi, (abs0 + slot) * d.n_features + f0 + fi, lane, g, h);
+            wave_best_cut(d, prm, node, f0 + fi, (abs0 + slot) * d.n_features + f0 + fi, lane, g, h,
+                          cut_scratch + (threadIdx.x >> 6) * kCutScratchBytes);
         }
     } else {
         for (int i = threadIdx.x; i < pairs * kBins; i += kHistThreads) {
@@ -432,37 +523,50 @@ __device__ __forceinline__ void hist_run(const TrainDesc &d, const Params &prm,
 template <bool PACKED>
 __global__ void __launch_bounds__(kHistThreads)
 train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, int rows_per_slab,
-                  int n_slabs, int hb, Params prm)
+                  int n_slabs, int hb, int sorted, Params prm)
 {
-    extern __shared__ unsigned long long lds_hist[];
+    extern __shared__ unsigned long long lds_raw[];              // cut-search scratch, then the histograms
+    unsigned char *cut_scratch = (unsigned char *)lds_raw;
+    unsigned long long *lds_hist = lds_raw + kHistCutScratch / 8;
     const TrainDesc &d = descs[blockIdx.z / passes];
     const int pass = blockIdx.z % passes;
-    const int row0 = blockIdx.x * rows_per_slab;
+    int row0 = blockIdx.x * rows_per_slab;
     const int f0 = blockIdx.y * 4;
     if (row0 >= d.n_rows || f0 >= d.n_features)
         return;
-    const int row1 = min(row0 + rows_per_slab, d.n_rows);
+    int row1 = min(row0 + rows_per_slab, d.n_rows);
     const int nf = min(4, d.n_features - f0);
     const int n_slots = 1 << level;
     const int slots = min(PACKED ? kHistSlotsPacked : kHistSlotsWide, n_slots);
     const int abs0 = pass * slots;                               // first node of the pass, within the level
     const int node0 = n_slots - 1 + abs0;                        // its heap index
+    if (sorted) {
+        // regrouped rows (one slab): the segments of this pass's ancestors on level kSortLevel
+        const int up = level - kSortLevel;
+        row0 = d.seg_start[abs0 >> up];
+        row1 = d.seg_start[((abs0 + slots - 1) >> up) + 1];
+    }
     int hot[4];
 #pragma unroll
     for (int fi = 0; fi < 4; ++fi)
         hot[fi] = fi < nf ? d.hot_bin[f0 + fi] : 256;           // 256: no bin, nothing is skipped
-    const uint32_t *__restrict__ words = (const uint32_t *)d.bins + (int64_t)blockIdx.y * d.r_pad;
+    const uint32_t *__restrict__ words =
+        (const uint32_t *)(sorted ? d.s_bins : d.bins) + (int64_t)blockIdx.y * d.r_pad;
+    const uint16_t *__restrict__ node_of = sorted ? d.s_node : d.node_of_row;
+    const int2 *__restrict__ qh_of = sorted ? d.s_qh : d.qh;
     if (PACKED) {
         if (*d.abs_q < (1ull << (63 - hb))) {
-            hist_run<true>(d, prm, lds_hist, node0, abs0, slots, row0, row1, f0, nf, hot, words, n_slabs, hb);
+            hist_run<true>(d, prm, lds_hist, node0, abs0, slots, row0, row1, f0, nf, hot, words, node_of, qh_of,
+                           n_slabs, hb, cut_scratch);
         } else {
             const int half = slots > 1 ? slots / 2 : 1;          // the wide form takes twice the LDS per node
             for (int s = 0; s < slots; s += half)
                 hist_run<false>(d, prm, lds_hist, node0 + s, abs0 + s, half, row0, row1, f0, nf, hot, words,
-                                n_slabs, 0);
+                                node_of, qh_of, n_slabs, 0, cut_scratch);
         }
     } else {
-        hist_run<false>(d, prm, lds_hist, node0, abs0, slots, row0, row1, f0, nf, hot, words, n_slabs, 0);
+        hist_run<false>(d, prm, lds_hist, node0, abs0, slots, row0, row1, f0, nf, hot, words, node_of, qh_of,
+                        n_slabs, 0, cut_scratch);
     }
 }
 
@@ -475,6 +579,7 @@ constexpr int kSplitWaves = 4;
 __global__ void __launch_bounds__(64 * kSplitWaves)
 train_split_kernel(const TrainDesc *__restrict__ descs, int level, Params prm)
 {
+    __shared__ __align__(8) unsigned char s_cut_scratch[kSplitWaves][kCutScratchBytes];
     const TrainDesc &d = descs[blockIdx.z];
     const int lane = threadIdx.x & 63;
     const int pair = blockIdx.x * kSplitWaves + (threadIdx.x >> 6);
@@ -495,7 +600,7 @@ train_split_kernel(const TrainDesc *__restrict__ descs, int level, Params prm)
         h[k] = (long long)v.y;
         hp[k] = (u64x2){0ull, 0ull};
     }
-    wave_best_cut(d, prm, node, f, pair, lane, g, h);
+    wave_best_cut(d, prm, node, f, pair, lane, g, h, s_cut_scratch[threadIdx.x >> 6]);
 }
 
 // Per open node of the level: best feature, split or leaf; children get consecutive ids in
@@ -614,13 +719,140 @@ train_part_kernel(const TrainDesc *__restrict__ descs, int level)
     d.node_of_row[r] = (uint16_t)(2 * node + (b < d.h_cut[node] ? 1 : 2));
 }
 
+// The same for regrouped rows (levels from kSortLevel on): positions instead of rows.
 __global__ void __launch_bounds__(256)
-train_update_kernel(const TrainDesc *__restrict__ descs)
+train_part_sorted_kernel(const TrainDesc *__restrict__ descs, int level)
+{
+    const TrainDesc &d = descs[blockIdx.y];
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= d.seg_start[kSortSegs])
+        return;
+    const int node = d.s_node[p];
+    if (node < (1 << level) - 1 || d.h_state[node] != kInternal)
+        return;
+    const int f = d.h_feat[node];
+    const int b = d.s_bins[((int64_t)(f >> 2) * d.r_pad + p) * 4 + (f & 3)];
+    d.s_node[p] = (uint16_t)(2 * node + (b < d.h_cut[node] ? 1 : 2));
+}
+
+// Regrouping, step 1: rows per node of level kSortLevel (rows that stopped in a leaf above
+// that level stay behind).  seg_cursor is zero when the tree begins.
+__global__ void __launch_bounds__(256)
+train_seg_count_kernel(const TrainDesc *__restrict__ descs)
+{
+    __shared__ int s_cnt[kSortSegs];
+    const TrainDesc &d = descs[blockIdx.y];
+    if (blockIdx.x * blockDim.x >= (unsigned)d.n_rows)
+        return;
+    if (threadIdx.x < kSortSegs)
+        s_cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < d.n_rows) {
+        const int seg = (int)d.node_of_row[r] - (kSortSegs - 1);
+        if (seg >= 0 && seg < kSortSegs)
+            atomicAdd(&s_cnt[seg], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x < kSortSegs && s_cnt[threadIdx.x] != 0)
+        atomicAdd(&d.seg_cursor[threadIdx.x], s_cnt[threadIdx.x]);
+}
+
+// Step 2: seg_start = exclusive scan of the counts; seg_cursor = the same (fill positions).
+__global__ void __launch_bounds__(64)
+train_seg_scan_kernel(const TrainDesc *__restrict__ descs)
+{
+    static_assert(kSortSegs <= 64, "one wavefront scans the segments");
+    const TrainDesc &d = descs[blockIdx.x];
+    const int t = threadIdx.x;
+    const int mine = t < kSortSegs ? d.seg_cursor[t] : 0;
+    int incl = mine;
+    for (int off = 1; off < 64; off <<= 1) {
+        const int u = __shfl_up(incl, off);
+        if (t >= off)
+            incl += u;
+    }
+    if (t < kSortSegs) {
+        d.seg_start[t] = incl - mine;
+        d.seg_cursor[t] = incl - mine;
+    }
+    if (t == kSortSegs - 1)
+        d.seg_start[kSortSegs] = incl;
+}
+
+// Step 3: a position for every row that goes on (order inside a segment is free: all sums over
+// rows are integer sums); its node, gradient pair and row number move there.
+__global__ void __launch_bounds__(256)
+train_seg_place_kernel(const TrainDesc *__restrict__ descs)
+{
+    __shared__ int s_cnt[kSortSegs], s_base[kSortSegs];
+    const TrainDesc &d = descs[blockIdx.y];
+    if (blockIdx.x * blockDim.x >= (unsigned)d.n_rows)
+        return;
+    if (threadIdx.x < kSortSegs)
+        s_cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    int seg = -1, rank = 0, node = 0;
+    if (r < d.n_rows) {
+        node = d.node_of_row[r];
+        seg = node - (kSortSegs - 1);
+        if (seg >= kSortSegs)
+            seg = -1;                                            // cannot happen: no row is below this level yet
+        if (seg >= 0)
+            rank = atomicAdd(&s_cnt[seg], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x < kSortSegs && s_cnt[threadIdx.x] != 0)
+        s_base[threadIdx.x] = atomicAdd(&d.seg_cursor[threadIdx.x], s_cnt[threadIdx.x]);
+    __syncthreads();
+    if (r < d.n_rows) {
+        int p = -1;
+        if (seg >= 0) {
+            p = s_base[seg] + rank;
+            d.s_rowid[p] = r;
+            d.s_node[p] = (uint16_t)node;
+            d.s_qh[p] = d.qh[r];
+        }
+        d.s_dest[r] = p;
+    }
+}
+
+// Step 4: the bins follow, one 32-bit word (four features) per thread.
+__global__ void __launch_bounds__(256)
+train_seg_bins_kernel(const TrainDesc *__restrict__ descs)
+{
+    const TrainDesc &d = descs[blockIdx.z];
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= d.n_rows || (int)blockIdx.y * 4 >= d.n_features)
+        return;
+    const int p = d.s_dest[r];
+    if (p < 0)
+        return;
+    const int64_t g = (int64_t)blockIdx.y * d.r_pad;
+    ((uint32_t *)d.s_bins)[g + p] = ((const uint32_t *)d.bins)[g + r];
+}
+
+// Row outputs += value of the leaf that holds the row.  With regrouped rows (`sorted`), the
+// rows that went on below kSortLevel are updated through their regrouped record, the others
+// (in a leaf above that level) through node_of_row.
+__global__ void __launch_bounds__(256)
+train_update_kernel(const TrainDesc *__restrict__ descs, int sorted)
 {
     const TrainDesc &d = descs[blockIdx.y];
     const int r = blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= d.n_rows)
         return;
+    if (sorted) {
+        if (r < d.seg_start[kSortSegs]) {
+            const int row = d.s_rowid[r];
+            d.row_pred[row] = d.row_pred[row] + d.h_val[d.s_node[r]];
+        }
+        const int node = d.node_of_row[r];
+        if (node < kSortSegs - 1)
+            d.row_pred[r] = d.row_pred[r] + d.h_val[node];
+        return;
+    }
     d.row_pred[r] = d.row_pred[r] + d.h_val[d.node_of_row[r]];
 }
 
@@ -900,6 +1132,23 @@ static int ensure_hist(fs_trainer *t, hipStream_t stream)
     return check_launch("train_fill_kernel launch");
 }
 
+// Buffers for the rows regrouped by node (deep trees).
+static int ensure_sort(fs_trainer *t)
+{
+    if (t->h.s_bins)
+        return FS_OK;
+    TrainDesc &h = t->h;
+    const size_t groups = ((size_t)h.n_features + 3) / 4;
+    int rc = dev_alloc(t, &h.s_qh, (size_t)h.n_rows);
+    if (rc == FS_OK) rc = dev_alloc(t, &h.s_rowid, (size_t)h.n_rows);
+    if (rc == FS_OK) rc = dev_alloc(t, &h.s_node, (size_t)h.n_rows);
+    if (rc == FS_OK) rc = dev_alloc(t, &h.s_dest, (size_t)h.n_rows);
+    if (rc == FS_OK) rc = dev_alloc(t, &h.seg_start, (size_t)kSortSegs + 1);
+    if (rc == FS_OK) rc = dev_alloc(t, &h.seg_cursor, (size_t)kSortSegs);
+    if (rc == FS_OK) rc = dev_alloc(t, &h.s_bins, groups * (size_t)h.r_pad * 4);   // last: marks the set complete
+    return rc;
+}
+
 // Uploads the batch's descriptors; returns the device array.
 static int upload_batch(int n, fs_trainer *const *trainers, hipStream_t stream, const TrainDesc **d_out)
 {
@@ -1006,6 +1255,15 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
     if (n_slabs > 1)
         for (int i = 0; i < n_trainers && rc == FS_OK; ++i)
             rc = ensure_hist(trainers[i], stream);
+    // deep trees of one-slab families: rows regrouped by node before level kSortLevel
+    bool use_sort = n_slabs == 1 && p->max_depth >= kSortMinDepth;
+    if (const char *e = getenv("FS_TUNE_TRAIN_SORT")) {          // tuning / test aid: 0 never, 1 whenever possible
+        const int v = atoi(e);
+        use_sort = n_slabs == 1 && v != 0 && p->max_depth > kSortLevel;
+    }
+    if (use_sort)
+        for (int i = 0; i < n_trainers && rc == FS_OK; ++i)
+            rc = ensure_sort(trainers[i]);
     if (rc != FS_OK)
         return rc;
     const TrainDesc *d = nullptr;
@@ -1029,10 +1287,10 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
         if (!hist_configured[dev]) {
             FS_HIP(hipFuncSetAttribute((const void *)train_hist_kernel<true>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kHistSlotsPacked * 4 * kBins * 8));
+                                       kHistSlotsPacked * 4 * kBins * 8 + kHistCutScratch));
             FS_HIP(hipFuncSetAttribute((const void *)train_hist_kernel<false>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kHistSlotsWide * 4 * kBins * 16));
+                                       kHistSlotsWide * 4 * kBins * 16 + kHistCutScratch));
             hist_configured[dev] = true;
         }
     }
@@ -1060,6 +1318,7 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
         prof_stop(stream);
         for (int level = 0; level < prm.max_depth; ++level) {
             const int n_slots = 1 << level;
+            const int sorted = use_sort && level >= kSortLevel ? 1 : 0;
             const int per_pass = packed ? kHistSlotsPacked : kHistSlotsWide;
             const int slots = n_slots < per_pass ? n_slots : per_pass;
             const int passes = n_slots / slots;
@@ -1070,12 +1329,12 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
                 size_t lds = (size_t)slots * 4 * kBins * 8;
                 if (lds < (size_t)4 * kBins * 16)
                     lds = (size_t)4 * kBins * 16;
-                hipLaunchKernelGGL(train_hist_kernel<true>, hgrid, dim3(kHistThreads), lds, stream, d, level,
-                                   passes, rows_per_slab, n_slabs, hb, prm);
+                hipLaunchKernelGGL(train_hist_kernel<true>, hgrid, dim3(kHistThreads), lds + kHistCutScratch,
+                                   stream, d, level, passes, rows_per_slab, n_slabs, hb, sorted, prm);
             } else {
                 hipLaunchKernelGGL(train_hist_kernel<false>, hgrid, dim3(kHistThreads),
-                                   (size_t)slots * 4 * kBins * 16, stream, d, level, passes, rows_per_slab,
-                                   n_slabs, 0, prm);
+                                   (size_t)slots * 4 * kBins * 16 + kHistCutScratch, stream, d, level, passes,
+                                   rows_per_slab, n_slabs, 0, sorted, prm);
             }
             prof_stop(stream);
             prof_start(kKernTrainSplit, stream);
@@ -1086,13 +1345,24 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
             hipLaunchKernelGGL(train_pick_kernel, dim3(nt), dim3(kPickThreads), 0, stream, d, level, prm);
             prof_stop(stream);
             prof_start(kKernTrainOther, stream);
-            hipLaunchKernelGGL(train_part_kernel, dim3(row_blocks, nt), dim3(256), 0, stream, d, level);
+            if (sorted)
+                hipLaunchKernelGGL(train_part_sorted_kernel, dim3(row_blocks, nt), dim3(256), 0, stream, d, level);
+            else
+                hipLaunchKernelGGL(train_part_kernel, dim3(row_blocks, nt), dim3(256), 0, stream, d, level);
+            if (use_sort && level == kSortLevel - 1) {
+                hipLaunchKernelGGL(train_seg_count_kernel, dim3(row_blocks, nt), dim3(256), 0, stream, d);
+                hipLaunchKernelGGL(train_seg_scan_kernel, dim3(nt), dim3(64), 0, stream, d);
+                hipLaunchKernelGGL(train_seg_place_kernel, dim3(row_blocks, nt), dim3(256), 0, stream, d);
+                hipLaunchKernelGGL(train_seg_bins_kernel, dim3(row_blocks, (unsigned)((max_feat + 3) / 4), nt),
+                                   dim3(256), 0, stream, d);
+            }
             prof_stop(stream);
         }
         prof_start(kKernTrainOther, stream);
         hipLaunchKernelGGL(train_pick_kernel, dim3(nt), dim3(kPickThreads), 0, stream, d,
                            prm.max_depth, prm);
-        hipLaunchKernelGGL(train_update_kernel, dim3(row_blocks, nt), dim3(256), 0, stream, d);
+        hipLaunchKernelGGL(train_update_kernel, dim3(row_blocks, nt), dim3(256), 0, stream, d,
+                           use_sort ? 1 : 0);
         hipLaunchKernelGGL(train_emit_kernel, dim3(nt), dim3(512), 0, stream, d);
         prof_stop(stream);
         rc = check_launch("training kernels launch");

@@ -222,3 +222,34 @@ def test_histogram_forms_packed_wide_and_fallback(api, T, monkeypatch):
     check(api, T, ts, **kw)                                          # packed, several slabs
     check(api, T, huge, rounds=2, max_depth=5, eta=0.5, lam=1.0)      # fallback, several slabs
     monkeypatch.delenv("FS_TUNE_TRAIN_SLAB_ROWS")
+
+
+def test_rows_regrouped_by_node_for_deep_trees(api, T, monkeypatch):
+    """From depth 7 on the rows are regrouped once per tree by their node of level 5 and the
+    deeper histograms read only their ancestors' segments; the trees must not change.  Forced on
+    at depth 6, forced off at depth 9, and run with early leaves above level 5 (rows that stay
+    behind) and with several families of different sizes in one batch."""
+    import torch
+    ts = W.make_train_set(43, 3000, stmts=(1, 9), n_features=17, max_cuts=200)
+    monkeypatch.setenv("FS_TUNE_TRAIN_SORT", "1")
+    check(api, T, ts, rounds=3, max_depth=6, eta=0.5, lam=1.0)
+    check(api, T, ts, rounds=2, max_depth=9, eta=0.5, lam=0.0, min_child_weight=40.0)   # leaves above level 5
+    monkeypatch.setenv("FS_TUNE_TRAIN_PACKED", "0")
+    check(api, T, ts, rounds=2, max_depth=8, eta=0.5, lam=1.0)                          # 8 nodes per pass
+    monkeypatch.delenv("FS_TUNE_TRAIN_PACKED")
+    monkeypatch.setenv("FS_TUNE_TRAIN_SORT", "0")
+    check(api, T, ts, rounds=2, max_depth=9, eta=0.5, lam=1.0)
+    monkeypatch.delenv("FS_TUNE_TRAIN_SORT")
+    sets = [W.make_train_set(50 + i, n, stmts=(1, 6), n_features=9, max_cuts=60) for i, n in enumerate((400, 2500, 60))]
+    p = api.train_params(max_depth=8, eta=0.4, lam=1.0)
+    trs = [api.fs_trainer.from_train_set(s, max_depth=8, max_trees=3) for s in sets]
+    api.fs_train_boost(trs, 3, p)
+    torch.cuda.synchronize()
+    for s, tr in zip(sets, trs):
+        exp = T.train(s.features, s.prog_off, s.target, s.cut_off, s.cuts, bias=0.0, n_rounds=3, max_depth=8,
+                      eta=p.eta, lam=p.lam, min_gain=p.min_gain, min_child_weight=p.min_child_weight,
+                      grad_scale=p.grad_scale)
+        same_trees(tr.export(), exp)
+        rows, progs = tr.predictions()
+        torch.cuda.synchronize()
+        assert np.array_equal(rows.cpu().numpy().view(np.uint32), exp.row_pred.view(np.uint32))
