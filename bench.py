@@ -162,7 +162,7 @@ def train_main(args, np, torch, api, W):
                    "rows": n_rows, "programs": n_prog, "features": n_feat},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
-                     "kernel": "train_zero_hist_kernel+train_hist_kernel (one level)",
+                     "kernel": "train_hist_kernel (one level)",
                      "kernel_avg_ms": round(hist_avg, 5),
                      "algorithmic_bytes_per_launch": int(alg_bytes)},
         "kernels_ms_per_step": {k: round(v[0] / max(1, args.steps), 5) for k, v in prof.items()
