@@ -12,11 +12,14 @@
 //   begin_tree   clear the heap of the tree to grow
 //   grad         per program: s_p (row order), g_p, q_p; rows get (q_p, rows of p) and go
 //                back to the root; the root's (G, H) are added up on the way
-//   per level:   hist (LDS histograms per row slab and feature group, flushed with 64-bit
-//                atomics; a feature's most frequent bin is never counted, it is the node's
-//                total minus the rest), split (one wavefront per (node, feature): scan the
-//                bins, best cut, clear the histogram), pick (per node: best feature, split or leaf, child ids in
-//                breadth-first order), part (rows of split nodes move to a child)
+//   per level:   hist (LDS histograms per family, four features and up to 16 nodes; a
+//                feature's most frequent bin is never counted, it is the node's total minus
+//                the rest; with one slab of rows per family the same workgroup then finds the
+//                best cut of each (node, feature), else the slabs add into a global buffer and
+//                `split` searches there), pick (per node: best feature, split or leaf, child
+//                ids in breadth-first order), part (rows of split nodes move to a child)
+//   deep trees:  before level 5 the rows are regrouped once by their node (seg_*), so that
+//                deeper histogram passes read only the segments of their nodes' ancestors
 //   pick         once more at max_depth: what is left becomes leaves
 //   update       row output += value of the row's leaf;  emit: heap -> flat model arrays
 #include <math.h>
