@@ -516,7 +516,9 @@ extern "C" int fs_topk(int32_t n_requests, const fs_topk_req *reqs, void *stream
             if (p.s * kp > max_comp)
                 max_comp = p.s * kp;
         } else if (p.mode == 2) {
-            comp_total += (size_t)r.n;                       // first-stage lists: at most every entry
+            // first-stage lists: min(k, length) per slice
+            const size_t every = (size_t)r.n, capped = (size_t)p.s * (size_t)r.k;
+            comp_total += every < capped ? every : capped;
             int lists = p.s, levels = 0;
             while (lists > 1) {
                 const int pairs = lists / 2;

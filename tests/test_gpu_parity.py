@@ -250,6 +250,7 @@ def test_topk_wide_cuts_merge_in_global_memory(api, oracle):
     step[93000:] = 2.0                                                       # best entries in the last slices
     cases.append((step, 8000))
     cases.append((rng.standard_normal(700000).astype(np.float32), 16384))    # 128 slices of 5504 (cap)
+    cases.append((rng.standard_normal(3_000_000).astype(np.float32), 16384))  # slices longer than the cut
     cases.append((np.full(9000, np.nan, np.float32), 6000))
     cases.append((rng.standard_normal(30000).astype(np.float32), 100))       # LDS merge, same launch
     cases.append((rng.standard_normal(500).astype(np.float32), 20))          # short, same launch
