@@ -72,6 +72,8 @@ struct TrainDesc {
     long long *best_GL, *best_HL;
     int32_t *counters;         // [0] next node id of the tree in work, [1] trees, [2] nodes
     unsigned long long *abs_q; // sum over the rows of |gradient| (fixed point) of the round in work
+    int32_t *pk_feat, *pk_cut; // per node of a level: its best feature and cut (levels with many nodes)
+    double *pk_gain;
     // Rows regrouped by their node of level kSortLevel (deep trees only, see train_seg_* below):
     uint8_t *s_bins;           // bins in that order, same layout as `bins`
     int2 *s_qh;
@@ -613,9 +615,64 @@ train_split_kernel(const TrainDesc *__restrict__ descs, int level, Params prm)
 constexpr int kPickThreads = 1024;
 constexpr int kMaxSlots = 1 << FS_TRAIN_MAX_DEPTH;
 static_assert(kMaxSlots <= kPickThreads, "one thread per node of the deepest level");
+constexpr int kPickSpreadSlots = 64;     // levels with at least this many nodes reduce in a kernel of their own
+
+// Best feature of node number `sl` of the level, by one wavefront (lanes over the features):
+// largest gain, lowest feature on ties.  No candidate: feature -1.
+__device__ __forceinline__ void wave_best_feature(const TrainDesc &d, int level, const Params &prm, int sl,
+                                                  int lane, int &bf, int &bc, double &bg)
+{
+    const int n_slots = 1 << level;
+    bf = -1;
+    bc = 0;
+    bg = 0.0;
+    if (level < prm.max_depth && d.h_state[n_slots - 1 + sl] == kOpen) {
+        for (int f = lane; f < d.n_features; f += 64) {          // ascending: first of equals stays
+            const int64_t o = (int64_t)sl * d.n_features + f;
+            const int c = d.best_cut[o];
+            if (c == 0)
+                continue;
+            const double g = d.best_gain[o];
+            if (bf < 0 || g > bg) {
+                bg = g;
+                bf = f;
+                bc = c;
+            }
+        }
+        for (int off = 32; off > 0; off >>= 1) {                 // largest gain, lowest feature on ties
+            const double og = __shfl_xor(bg, off);
+            const int of = __shfl_xor(bf, off), oc = __shfl_xor(bc, off);
+            if (of >= 0 && (bf < 0 || og > bg || (og == bg && of < bf))) {
+                bg = og;
+                bf = of;
+                bc = oc;
+            }
+        }
+    }
+}
+
+// Levels with many nodes: the best feature of every node, one wavefront each, over the whole
+// chip (train_pick_kernel, one workgroup per trainer, then only decides).
+__global__ void __launch_bounds__(kPickThreads)
+train_pick_reduce_kernel(const TrainDesc *__restrict__ descs, int level, Params prm)
+{
+    const TrainDesc &d = descs[blockIdx.y];
+    const int lane = threadIdx.x & 63;
+    const int sl = blockIdx.x * (kPickThreads / 64) + (threadIdx.x >> 6);
+    if (sl >= (1 << level))
+        return;
+    int bf, bc;
+    double bg;
+    wave_best_feature(d, level, prm, sl, lane, bf, bc, bg);
+    if (lane == 0) {
+        d.pk_feat[sl] = bf;
+        d.pk_cut[sl] = bc;
+        d.pk_gain[sl] = bg;
+    }
+}
 
 __global__ void __launch_bounds__(kPickThreads)
-train_pick_kernel(const TrainDesc *__restrict__ descs, int level, Params prm)
+train_pick_kernel(const TrainDesc *__restrict__ descs, int level, int reduced, Params prm)
 {
     __shared__ int s_scan[kMaxSlots];
     __shared__ int s_bf[kMaxSlots], s_bc[kMaxSlots];
@@ -623,36 +680,22 @@ train_pick_kernel(const TrainDesc *__restrict__ descs, int level, Params prm)
     const TrainDesc &d = descs[blockIdx.x];
     const int n_slots = 1 << level;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int sl = wave; sl < n_slots; sl += kPickThreads / 64) {
-        int bf = -1, bc = 0;
-        double bg = 0.0;
-        if (level < prm.max_depth && d.h_state[n_slots - 1 + sl] == kOpen) {
-            for (int f = lane; f < d.n_features; f += 64) {      // ascending: first of equals stays
-                const int64_t o = (int64_t)sl * d.n_features + f;
-                const int c = d.best_cut[o];
-                if (c == 0)
-                    continue;
-                const double g = d.best_gain[o];
-                if (bf < 0 || g > bg) {
-                    bg = g;
-                    bf = f;
-                    bc = c;
-                }
-            }
-            for (int off = 32; off > 0; off >>= 1) {             // largest gain, lowest feature on ties
-                const double og = __shfl_xor(bg, off);
-                const int of = __shfl_xor(bf, off), oc = __shfl_xor(bc, off);
-                if (of >= 0 && (bf < 0 || og > bg || (og == bg && of < bf))) {
-                    bg = og;
-                    bf = of;
-                    bc = oc;
-                }
-            }
+    if (reduced) {
+        if ((int)threadIdx.x < n_slots) {
+            s_bf[threadIdx.x] = d.pk_feat[threadIdx.x];
+            s_bc[threadIdx.x] = d.pk_cut[threadIdx.x];
+            s_bg[threadIdx.x] = d.pk_gain[threadIdx.x];
         }
-        if (lane == 0) {
-            s_bf[sl] = bf;
-            s_bc[sl] = bc;
-            s_bg[sl] = bg;
+    } else {
+        for (int sl = wave; sl < n_slots; sl += kPickThreads / 64) {
+            int bf, bc;
+            double bg;
+            wave_best_feature(d, level, prm, sl, lane, bf, bc, bg);
+            if (lane == 0) {
+                s_bf[sl] = bf;
+                s_bc[sl] = bc;
+                s_bg[sl] = bg;
+            }
         }
     }
     __syncthreads();
@@ -1051,6 +1094,9 @@ extern "C" int fs_trainer_create(fs_trainer **out, int32_t n_features, const flo
     TRY(dev_alloc(t, &h.best_HL, (size_t)hist_slots * n_features));
     TRY(dev_alloc(t, &h.counters, (size_t)4));
     TRY(dev_alloc(t, &h.abs_q, (size_t)1));
+    TRY(dev_alloc(t, &h.pk_feat, (size_t)kMaxSlots));
+    TRY(dev_alloc(t, &h.pk_cut, (size_t)kMaxSlots));
+    TRY(dev_alloc(t, &h.pk_gain, (size_t)kMaxSlots));
     TRY(dev_alloc(t, &h.m_tree_off, (size_t)max_trees + 1));
     TRY(dev_alloc(t, &h.m_feat, (size_t)node_cap));
     TRY(dev_alloc(t, &h.m_left, (size_t)node_cap));
@@ -1345,7 +1391,14 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
                 hipLaunchKernelGGL(train_split_kernel,
                                    dim3((unsigned)((n_slots * max_feat + kSplitWaves - 1) / kSplitWaves), 1u, nt),
                                    dim3(64 * kSplitWaves), 0, stream, d, level, prm);
-            hipLaunchKernelGGL(train_pick_kernel, dim3(nt), dim3(kPickThreads), 0, stream, d, level, prm);
+            // from 64 nodes on the per-node reduction over the features gets the whole chip
+            const int reduced = n_slots >= kPickSpreadSlots ? 1 : 0;
+            if (reduced)
+                hipLaunchKernelGGL(train_pick_reduce_kernel,
+                                   dim3((unsigned)(n_slots / (kPickThreads / 64)), nt), dim3(kPickThreads), 0,
+                                   stream, d, level, prm);
+            hipLaunchKernelGGL(train_pick_kernel, dim3(nt), dim3(kPickThreads), 0, stream, d, level, reduced,
+                               prm);
             prof_stop(stream);
             prof_start(kKernTrainOther, stream);
             if (sorted)
@@ -1363,7 +1416,7 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
         }
         prof_start(kKernTrainOther, stream);
         hipLaunchKernelGGL(train_pick_kernel, dim3(nt), dim3(kPickThreads), 0, stream, d,
-                           prm.max_depth, prm);
+                           prm.max_depth, 0, prm);
         hipLaunchKernelGGL(train_update_kernel, dim3(row_blocks, nt), dim3(256), 0, stream, d,
                            use_sort ? 1 : 0);
         hipLaunchKernelGGL(train_emit_kernel, dim3(nt), dim3(512), 0, stream, d);
