@@ -140,6 +140,40 @@ bool tree_is_perfect(const int32_t *sf, const int32_t *left, const int32_t *righ
 
 // Largest chunk image: node offsets are 16 bits, and the kernel stages the next chunk in
 // kPrefetchRegs 16-byte registers per thread.
+// How many trees a chunk should get.  The wavefronts that share a tile (`share` of them) split a
+// chunk's trees into runs of at most 8 and walk a run's trees side by side, so a chunk costs a
+// fixed part (copy, barriers, ordered sum), a part per run of its busiest wavefront (the
+// dependent LDS reads of one walk) and a part per tree of that wavefront.  Weights fitted to
+// measurements, in units of one chunk with one run of few trees: 0.73 fixed, 0.27 per run,
+// 0.175 per tree -- e.g. 25 trees over 3 wavefronts are two runs each where 24 are one.  Two
+// plans are priced: equal chunks, and chunks that are a multiple of `share` x 8 or of `share`
+// with the remainder in a last short chunk; the second is taken if it is clearly cheaper.
+// Returns the trees per chunk (`fit` = how many fit in LDS).
+static int chunk_tree_target(int n_trees, int fit, int share)
+{
+    auto cost = [share](int n) {
+        const int groups = share * ((n + 8 * share - 1) / (8 * share));
+        const int runs = groups / share, per = (n + groups - 1) / groups;
+        return 0.73 + runs * (0.27 + 0.175 * per);
+    };
+    if (fit < 1) fit = 1;
+    const int even_chunks = (n_trees + fit - 1) / fit;
+    const int even = (n_trees + even_chunks - 1) / even_chunks;
+    double best_cost = even_chunks * cost(even);
+    int best = even;
+    const int step = fit >= 8 * share ? 8 * share : share;
+    const int whole = fit / step * step;
+    if (whole >= step) {
+        const int full = n_trees / whole, rest = n_trees - full * whole;
+        const double c = full * cost(whole) + (rest ? cost(rest) : 0.0);
+        if (c < 0.95 * best_cost) {
+            best_cost = c;
+            best = whole;
+        }
+    }
+    return best;
+}
+
 size_t chunk_image_limit(int mode)
 {
     const size_t by_regs = (size_t)kLdsModeWaves[mode] * 64 * kPrefetchRegs * 16;
@@ -247,7 +281,7 @@ void build_rank_format(fs_model *m, int n_features, int n_trees, int depth, cons
     m->rank_ok = true;
     m->rk_depth = depth;
     m->rk_tiles = best_t;
-    m->rk_trees_per_chunk = best_per;
+    m->rk_trees_per_chunk = chunk_tree_target(n_trees, best_per, kRankWaves / best_t);
     m->rk_tree_bytes = (int32_t)tree_bytes;
     m->rk_tile0 = kRankLdsBytes - best_t * (int32_t)tile_bytes;
     m->cut_bits = bits;
@@ -441,16 +475,14 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                 m->compact = compact;
                 m->lds_tiles = best_t;
                 m->lds_mode = best_mode;
-                // Even chunks: a greedy fill would leave a short last chunk whose few trees cannot
-                // keep the wavefronts busy.  Estimate the chunk count from the average tree and
-                // cap every chunk at ceil(n_trees / chunks).
+                // Trees per chunk: estimated from the average tree, then balanced over the
+                // wavefronts that share a tile (chunk_tree_target).
                 size_t est_per = best_avail / (avg_tree + 4 + per_tree_val);
                 const size_t est_img = (chunk_image_limit(best_mode) - 16) / (avg_tree + 4);
                 if (est_per > est_img) est_per = est_img;
                 if (est_per > (size_t)kMaxChunkTrees) est_per = kMaxChunkTrees;
                 if (est_per < 1) est_per = 1;
-                const int est_chunks = (int)(((size_t)n_trees + est_per - 1) / est_per);
-                const int even_cap = (n_trees + est_chunks - 1) / est_chunks;
+                const int even_cap = chunk_tree_target(n_trees, (int)est_per, kLdsModeWaves[best_mode] / best_t);
                 int t = 0;
                 while (t < n_trees) {
                     // how many trees fit: chunk image (table included) + their value rows
