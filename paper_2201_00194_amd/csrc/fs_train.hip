@@ -24,6 +24,7 @@
 //   update       row output += value of the row's leaf;  emit: heap -> flat model arrays
 #include <math.h>
 #include <stdlib.h>
+#include <algorithm>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -1226,8 +1227,21 @@ static int upload_batch(int n, fs_trainer *const *trainers, hipStream_t stream, 
         FS_HIP(hipHostMalloc((void **)&b.h_desc, sizeof(TrainDesc) * (size_t)cap, hipHostMallocDefault));
         b.cap = cap;
     }
+    // Largest families first: the histogram launches have a workgroup per (family, four
+    // features), a little more than one per compute unit, and those dispatched last should be
+    // the short ones.  (The order of the descriptors is internal; kernels index by block.)
+    std::vector<int> order;
+    try {
+        order.resize((size_t)n);
+    } catch (...) {
+        return fail(FS_ENOMEM, "out of host memory");
+    }
     for (int i = 0; i < n; ++i)
-        b.h_desc[i] = trainers[i]->h;
+        order[(size_t)i] = i;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int a, int c) { return trainers[a]->h.n_rows > trainers[c]->h.n_rows; });
+    for (int i = 0; i < n; ++i)
+        b.h_desc[i] = trainers[order[(size_t)i]]->h;
     FS_HIP(hipMemcpyAsync(b.d_desc, b.h_desc, sizeof(TrainDesc) * (size_t)n, hipMemcpyHostToDevice, stream));
     FS_HIP(hipEventRecord(b.copied, stream));
     b.pending = true;
