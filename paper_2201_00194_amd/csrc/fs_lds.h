@@ -35,5 +35,52 @@ static __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_r
 
 static __device__ __forceinline__ uint32_t lds_u16(uint32_t a) { return *FS_LDS_PTR(const uint16_t, a); }
 
+// acc += B parked values, `stride` bytes apart from LDS address `va` on, in that order: all B
+// loads go out before the first add (their addresses are immediates), so the ordered sum
+// exposes the LDS latency once per call.  The caller takes the largest B that fits first.
+template <int B>
+__device__ __forceinline__ void ordered_add(float &acc, uint32_t &va, uint32_t stride)
+{
+    float v[B];
+#pragma unroll
+    for (int k = 0; k < B; ++k)
+        v[k] = lds_f(va + (uint32_t)k * stride);
+#pragma unroll
+    for (int k = 0; k < B; ++k)
+        acc = acc + v[k];
+    va += (uint32_t)B * stride;
+}
+
+// The same for n values, n >= 0.
+__device__ __forceinline__ void ordered_add_n(float &acc, uint32_t va, uint32_t stride, int n)
+{
+    while (n >= 32) {
+        ordered_add<32>(acc, va, stride);
+        n -= 32;
+    }
+    if (n >= 24) {
+        ordered_add<24>(acc, va, stride);
+        n -= 24;
+    }
+    if (n >= 16) {
+        ordered_add<16>(acc, va, stride);
+        n -= 16;
+    }
+    if (n >= 8) {
+        ordered_add<8>(acc, va, stride);
+        n -= 8;
+    }
+    if (n >= 4) {
+        ordered_add<4>(acc, va, stride);
+        n -= 4;
+    }
+    if (n >= 2) {
+        ordered_add<2>(acc, va, stride);
+        n -= 2;
+    }
+    if (n >= 1)
+        ordered_add<1>(acc, va, stride);
+}
+
 }  // namespace fs
 #endif

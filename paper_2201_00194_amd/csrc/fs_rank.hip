@@ -401,22 +401,8 @@ traverse_rank_kernel(const FamDesc *__restrict__ descs, int n_families)
         }
         __syncthreads();       // every walk of this chunk is done and its values are parked
         if (active && my_slot == 0) {
-            uint32_t va = val0 + (uint32_t)my_tile * 256u + 4u * (uint32_t)lane;
-            int t = 0;
-            for (; t + 8 <= n; t += 8) {                   // loads first, then the ordered adds
-                float v[8];
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    v[k] = lds_f(va + (uint32_t)k * val_stride);
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    acc = acc + v[k];
-                va += 8u * val_stride;
-            }
-            for (; t < n; ++t) {
-                acc = acc + lds_f(va);
-                va += val_stride;
-            }
+            const uint32_t va = val0 + (uint32_t)my_tile * 256u + 4u * (uint32_t)lane;
+            ordered_add_n(acc, va, val_stride, n);
         }
         if (c + 1 < n_chunks) {
             const int n16 = n_next * tree16;
