@@ -35,6 +35,36 @@ static __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_r
 
 static __device__ __forceinline__ uint32_t lds_u16(uint32_t a) { return *FS_LDS_PTR(const uint16_t, a); }
 
+// Linear copy global -> LDS without registers: every wavefront-wide group of 64 consecutive
+// 16-byte pieces (1 KB) goes out as one load whose data the memory pipeline writes straight to
+// LDS, lane l's piece at dst + 16*l (gfx950).  Wavefront `wave` of `n_waves` issues groups wave,
+// wave + n_waves, ...; returns the number of pieces covered (n16 rounded down to 64) -- the
+// caller copies the rest through registers.  Nothing is waited for: lds_direct_wait() before
+// the barrier that publishes the data.  `dst` must be the same in all lanes.
+// `src`: what FS_GLOBAL(const u32x4, ...) gives.
+template <class P>
+static __device__ __forceinline__ int lds_fill_direct(P src, uint32_t dst, int n16, int wave, int n_waves,
+                                                      int lane)
+{
+    const int n_groups = n16 >> 6;
+#if defined(__HIP_DEVICE_COMPILE__)
+    for (int g = wave; g < n_groups; g += n_waves)
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(src + (g << 6) + lane),
+            (__attribute__((address_space(3))) void *)(uint32_t)(dst + 1024u * (uint32_t)g), 16, 0, 0);
+#else
+    (void)src; (void)dst; (void)wave; (void)n_waves; (void)lane;   // host pass only parses the kernels
+#endif
+    return n_groups << 6;
+}
+
+static __device__ __forceinline__ void lds_direct_wait()
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_s_waitcnt(0);
+#endif
+}
+
 // acc += B parked values, `stride` bytes apart from LDS address `va` on, in that order: all B
 // loads go out before the first add (their addresses are immediates), so the ordered sum
 // exposes the LDS latency once per call.  The caller takes the largest B that fits first.

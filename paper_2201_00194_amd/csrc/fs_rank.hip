@@ -63,22 +63,15 @@ rank_code_kernel(const FamDesc *__restrict__ descs, int n_families)
     const int q = d.cut_bits;                       // table stride 2^q entries
     const int len = 1 << q;
 
-    // this group's padded threshold tables: one contiguous, 16-byte aligned run; all loads
-    // go out before the first LDS write
+    // this group's padded threshold tables: one contiguous, 16-byte aligned run, straight from
+    // memory to LDS (what is left below 64 pieces goes through a register)
     {
         auto cuts = FS_GLOBAL(const u32x4, d.cuts + (int64_t)f0 * len);
         const int n16 = gf * len / 4;
-        constexpr int kTabRegs = kBinTableBytes / 16 / kBinThreads;
-        u32x4 tb[kTabRegs];
-#pragma unroll
-        for (int j = 0; j < kTabRegs; ++j)
-            tb[j] = cuts[min(tid + j * kBinThreads, n16 - 1)];
-#pragma unroll
-        for (int j = 0; j < kTabRegs; ++j) {
-            const int i = tid + j * kBinThreads;
-            if (i < n16)
-                lds_store_u4(16u * (uint32_t)i, tb[j]);
-        }
+        const int rest = lds_fill_direct(cuts, 0u, n16, wave, kBinThreads / 64, lane) + tid;
+        if (rest < n16)
+            lds_store_u4(16u * (uint32_t)rest, cuts[rest]);
+        lds_direct_wait();
     }
     __syncthreads();
 
@@ -320,18 +313,19 @@ traverse_rank_kernel(const FamDesc *__restrict__ descs, int n_families)
     u32x4 pf[kRankPrefetchRegs];
     auto image = FS_GLOBAL(const u32x4, d.rk_nodes);
     const int tree16 = (int)(tree_bytes >> 4);
-    {
-        const int n16 = min(per_chunk, n_trees) * tree16;
-#pragma unroll
-        for (int j = 0; j < kRankPrefetchRegs; ++j)
-            pf[j] = image[min(tid + j * kRankThreads, n16 - 1)];
-    }
+    // The first chunk and the tiles go straight from memory to LDS, 1 KB per wavefront-wide
+    // load; what is left of each (fewer than 64 pieces) goes through registers.
+    const int first16 = min(per_chunk, n_trees) * tree16;
+    const int first_rest = lds_fill_direct(image, 0u, first16, wave, kRankWaves, lane) + tid;
+    if (first_rest < first16)
+        pf[0] = image[first_rest];
     // ---- rank tiles: consecutive tiles are one contiguous run ----
     {
         auto src = FS_GLOBAL(const u32x4, d.ranks + (int64_t)tile_first * Fc * 64);
         const int per_tile = Fc * 8;                       // 16-byte pieces per tile
         const int n16 = tiles_here * per_tile;
-        for (int base = tid; base < n16; base += kRankTileBatch * kRankThreads) {
+        const int done = lds_fill_direct(src, tile0, n16, wave, kRankWaves, lane);
+        for (int base = done + tid; base < n16; base += kRankTileBatch * kRankThreads) {
             u32x4 t4[kRankTileBatch];
 #pragma unroll
             for (int q = 0; q < kRankTileBatch; ++q)
@@ -344,15 +338,9 @@ traverse_rank_kernel(const FamDesc *__restrict__ descs, int n_families)
             }
         }
     }
-    {
-        const int n16 = min(per_chunk, n_trees) * tree16;
-#pragma unroll
-        for (int j = 0; j < kRankPrefetchRegs; ++j) {
-            const int i = tid + j * kRankThreads;
-            if (i < n16)
-                lds_store_u4(16u * (uint32_t)i, pf[j]);
-        }
-    }
+    if (first_rest < first16)
+        lds_store_u4(16u * (uint32_t)first_rest, pf[0]);
+    lds_direct_wait();
     __syncthreads();
 
     const int r = (tile_first + my_tile) * 64 + lane;

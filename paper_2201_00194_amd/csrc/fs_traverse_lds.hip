@@ -148,14 +148,23 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
     // ---- first chunk: global -> registers (lands while the tiles are being fetched) ----
     // Loads are unconditional with clamped indices (no branches between them, so they all go
     // out back to back); only the LDS writes are predicated.
+    // (Row-major input stages its rows at LDS offset 0 first, so there the chunk waits in
+    // registers; column-blocked input lets chunk and tiles go straight from memory to LDS.)
     u32x4 pf[kPrefetchRegs];
     ChunkHdr h = *FS_CONST(ChunkHdr, d.chunks);
+    const bool direct = d.layout != FS_ROWMAJOR;
     {
         auto src = FS_GLOBAL(const u32x4, d.image + h.byte_off);
         const int n16 = (int)(h.bytes >> 4);
+        if (direct) {
+            const int done = lds_fill_direct(src, 0u, n16, wave, kLdsWaves, lane);
+            if (done + tid < n16)
+                pf[0] = src[done + tid];                   // fewer than 64 pieces are left
+        } else {
 #pragma unroll
-        for (int j = 0; j < kPrefetchRegs; ++j)
-            pf[j] = src[min(tid + j * kLdsThreads, n16 - 1)];
+            for (int j = 0; j < kPrefetchRegs; ++j)
+                pf[j] = src[min(tid + j * kLdsThreads, n16 - 1)];
+        }
     }
     // ---- feature tiles ----
     if (d.layout == FS_ROWMAJOR) {
@@ -212,6 +221,15 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
         auto src = FS_GLOBAL(const u32x4, d.features + (int64_t)tile_first * F * 64);
         const int per_tile = F * 16;                       // 16-byte pieces per tile
         const int n16 = tiles_here * per_tile;
+        if ((per_tile & 63) == 0) {
+            // F % 4 == 0: every group of 64 pieces lies inside one tile
+            const int n_groups = n16 >> 6;
+            for (int g = wave; g < n_groups; g += kLdsWaves) {
+                const int i0 = g << 6;
+                const int t = i0 / per_tile, j0 = i0 - t * per_tile;
+                lds_fill_direct(src + i0, tile0 + (uint32_t)t * tile_bytes + 16u * (uint32_t)j0, 64, 0, 1, lane);
+            }
+        } else
         // two tiles are 7 pieces per thread: one batch, one exposure of the HBM latency
         for (int base = tid; base < n16; base += kTileBatch * kLdsThreads) {
             u32x4 t4[kTileBatch];
@@ -233,11 +251,18 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
     }
     {
         const int n16 = (int)(h.bytes >> 4);
-#pragma unroll
-        for (int j = 0; j < kPrefetchRegs; ++j) {
-            const int i = tid + j * kLdsThreads;
+        if (direct) {
+            const int i = (n16 & ~63) + tid;
             if (i < n16)
-                lds_store_u4(16u * (uint32_t)i, pf[j]);
+                lds_store_u4(16u * (uint32_t)i, pf[0]);
+            lds_direct_wait();
+        } else {
+#pragma unroll
+            for (int j = 0; j < kPrefetchRegs; ++j) {
+                const int i = tid + j * kLdsThreads;
+                if (i < n16)
+                    lds_store_u4(16u * (uint32_t)i, pf[j]);
+            }
         }
     }
     __syncthreads();
