@@ -133,9 +133,10 @@ typedef struct fs_family {
  * allowed.  Errors are detected on the host before anything is enqueued: FS_EINVAL
  * (NULL pointers, negative sizes, unknown layout, misaligned features), FS_ENOMEM /
  * FS_EDEVICE (scratch growth, launch failure).
- * When a family passes row_score == NULL the library uses its own scratch buffer, which
- * is shared by all calls on the device: such calls must not overlap in time on
- * different streams.
+ * The library keeps one scratch buffer per device (row scores of families that pass
+ * row_score == NULL, rank tiles of models it rank-codes, re-tiled copies of row-major
+ * input) which all calls on the device share: calls that use it -- in doubt, all calls of
+ * fs_score_families and fs_topk -- must not overlap in time on different streams.
  */
 int fs_score_families(int32_t n_families, const fs_family *fams /* HOST */, void *stream);
 
