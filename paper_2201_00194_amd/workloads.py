@@ -1,8 +1,11 @@
 """Seeded synthetic workloads: families of candidate programs and their cost models.
 
-This module only *draws inputs*.  It holds none of the scoring method's arithmetic
-(no traversal, no sums, no ranking) so that both the CPU oracle's tests and the
-HIP path's tests can take their inputs from it without sharing any of the method.
+This module only *draws inputs*.  It holds none of the method's arithmetic (no tree
+traversal, no sums of model outputs, no ranking, no training step) so that both the CPU
+oracle's tests and the HIP path's tests can take their inputs from it without sharing any
+of the method.  Training targets are drawn from a hidden closed-form response of the
+statements (step and product terms, `draw_response`) totalled per program: data for the
+trainers to fit, evaluated with whole-column numpy comparisons, never through a tree.
 
 The tuner the paper describes keeps one gradient-boosted-tree cost model per
 subgraph family (Section 4.2, Algorithm 1: one model initialised per family) and
@@ -401,29 +404,64 @@ class TrainSet:
         return int(self.prog_off.shape[0] - 1)
 
 
+@dataclass
+class Response:
+    """A hidden per-statement response used to draw synthetic measurement targets: a few step
+    terms a*[x[f] >= c] plus a few smooth terms w*x[f]*x[g].  It only makes targets that have
+    something to learn in them; it is not a model of the scoring method."""
+    step_feature: np.ndarray   # int64 [S]
+    step_cut: np.ndarray       # float32 [S]
+    step_amp: np.ndarray       # float64 [S]
+    pair_a: np.ndarray         # int64 [Q]
+    pair_b: np.ndarray         # int64 [Q]
+    pair_w: np.ndarray         # float64 [Q]
+
+    def rows(self, X: np.ndarray) -> np.ndarray:
+        """float64 response of every row of X."""
+        out = np.zeros(X.shape[0], np.float64)
+        for f, c, a in zip(self.step_feature, self.step_cut, self.step_amp):
+            out += a * (X[:, f] >= c)
+        for fa, fb, w in zip(self.pair_a, self.pair_b, self.pair_w):
+            out += w * (X[:, fa].astype(np.float64) * X[:, fb].astype(np.float64))
+        return out
+
+
+def draw_response(rng: np.random.Generator, probe: np.ndarray, steps: int = 60, pairs: int = 12,
+                  sigma: float = 0.1) -> Response:
+    """`steps` step terms whose cuts are values the probe rows themselves hold in that column
+    (so exact zeros are frequent cuts, as they are frequent values) and `pairs` product terms."""
+    n_rows, n_features = probe.shape
+    sf = rng.integers(0, n_features, size=steps)
+    sc = probe[rng.integers(0, max(1, n_rows), size=steps), sf].astype(np.float32)
+    sa = rng.standard_normal(steps) * sigma
+    pa = rng.integers(0, n_features, size=pairs)
+    pb = rng.integers(0, n_features, size=pairs)
+    pw = rng.standard_normal(pairs) * sigma
+    return Response(sf, sc, sa, pa, pb, pw)
+
+
+def _program_totals(rows: np.ndarray, off: np.ndarray) -> np.ndarray:
+    """Per-program totals of a per-row quantity (empty programs total 0)."""
+    n = off.shape[0] - 1
+    if n <= 0:
+        return np.zeros(0, np.float64)
+    c = np.concatenate([[0.0], np.cumsum(rows, dtype=np.float64)])
+    o = off.astype(np.int64)
+    return c[o[1:]] - c[o[:-1]]
+
+
 def make_train_set(seed: int, n_programs: int, stmts: Tuple[int, int] = (1, 16),
                    n_features: int = N_FEATURES, zero_frac: float = 0.3, max_cuts: int = 255,
-                   teacher_trees: int = 20, teacher_depth: int = 4, noise: float = 0.02) -> TrainSet:
-    """Synthetic measured programs: features as in the scoring workloads, targets = the
-    program score of a hidden random ensemble plus Gaussian noise (so there is something to
-    learn), rounded to float32."""
+                   steps: int = 60, pairs: int = 12, noise: float = 0.02) -> TrainSet:
+    """Synthetic measured programs: features as in the scoring workloads, targets = a hidden
+    step-plus-smooth response of the statements (`draw_response`), totalled per program, plus
+    Gaussian noise (so there is something to learn), rounded to float32."""
     rng = np.random.default_rng([seed, 4242])
     lo, hi = stmts
     off = uniform_prog_off(rng, n_programs, lo, hi) if hi > lo else fixed_prog_off(n_programs, lo)
     X = draw_features(rng, int(off[-1]), zero_frac, n_features=n_features)
-    teacher = draw_model(rng, X, teacher_trees, teacher_depth)
-    # the teacher's row outputs, by direct table walk over the full trees (heap order)
-    rows = np.zeros(X.shape[0], np.float64)
-    for t in range(teacher.n_trees):
-        o = int(teacher.tree_off[t])
-        node = np.zeros(X.shape[0], np.int64)
-        for _ in range(teacher_depth):
-            f = teacher.split_feature[o + node]
-            thr = teacher.threshold[o + node]
-            x = X[np.arange(X.shape[0]), f]
-            node = np.where(x < thr, teacher.left[o + node], teacher.right[o + node])
-        rows += teacher.value[o + node]
-    y = np.add.reduceat(rows, off[:-1].astype(np.int64)) if n_programs else np.zeros(0)
+    hidden = draw_response(rng, X, steps, pairs)
+    y = _program_totals(hidden.rows(X), off)
     y = y + rng.normal(0.0, noise, size=n_programs)
     cut_off, cuts = draw_cuts(X, max_cuts)
     return TrainSet(X, off, y.astype(np.float32), cut_off, cuts)
@@ -455,26 +493,12 @@ class Subgraph:
     val_target: np.ndarray     # float32 [P]
 
 
-def _teacher_rows(model: Model, X: np.ndarray, depth: int) -> np.ndarray:
-    rows = np.zeros(X.shape[0], np.float64)
-    ar = np.arange(X.shape[0])
-    for t in range(model.n_trees):
-        o = int(model.tree_off[t])
-        node = np.zeros(X.shape[0], np.int64)
-        for _ in range(depth):
-            f = model.split_feature[o + node]
-            node = np.where(X[ar, f] < model.threshold[o + node], model.left[o + node],
-                            model.right[o + node])
-        rows += model.value[o + node]
-    return rows
-
-
 def make_network(seed: int = 0, n_subgraphs: int = 11, n_families: int = 4, samples: int = 256,
                  val: int = 256, stmts: Tuple[int, int] = (1, 8), n_features: int = 32,
                  max_cuts: int = 63, own_weight: float = 0.35, noise: float = 0.02) -> List[Subgraph]:
     """A network in the shape of the paper's Section 3.1 study (11 subgraphs, 256 measured
-    candidates each).  Subgraphs of one family share a hidden teacher ensemble; every subgraph
-    adds a smaller teacher of its own (`own_weight`), so that pooling samples inside a family
+    candidates each).  Subgraphs of one family share a hidden response (`draw_response`); every
+    subgraph adds a smaller one of its own (`own_weight`), so that pooling samples inside a family
     helps, pooling across families hurts, and training alone starves.  All subgraphs share one
     cut list (drawn from the union of the training features) so that any model can score any
     subgraph's candidates."""
@@ -483,15 +507,14 @@ def make_network(seed: int = 0, n_subgraphs: int = 11, n_families: int = 4, samp
     fam_of[:n_families] = np.arange(n_families)              # every family has a member
     fam_of = np.sort(fam_of)
     probe = draw_features(rng, 2048, 0.3, n_features=n_features)
-    fam_teacher = [draw_model(rng, probe, 12, 4) for _ in range(n_families)]
+    fam_hidden = [draw_response(rng, probe, 48, 8) for _ in range(n_families)]
     parts = []
     for s in range(n_subgraphs):
-        own = draw_model(rng, probe, 6, 3, leaf_sigma=0.1 * own_weight / 0.35)
+        own = draw_response(rng, probe, 16, 4, sigma=0.1 * own_weight / 0.35)
         def pool(n_prog):
             off = uniform_prog_off(rng, n_prog, stmts[0], stmts[1])
             X = draw_features(rng, int(off[-1]), 0.3, n_features=n_features)
-            rows = _teacher_rows(fam_teacher[int(fam_of[s])], X, 4) + _teacher_rows(own, X, 3)
-            y = np.add.reduceat(rows, off[:-1].astype(np.int64))
+            y = _program_totals(fam_hidden[int(fam_of[s])].rows(X) + own.rows(X), off)
             return X, off, y
         Xt, offt, yt = pool(samples)
         Xv, offv, yv = pool(val)
