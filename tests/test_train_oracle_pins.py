@@ -182,3 +182,91 @@ def test_min_child_weight_and_min_gain_stop_splits(T):
     from oracle import oracle as O
     leaves = O.leaf_indices(m, ts.features)[:, 0]
     assert np.bincount(leaves).max() >= 8 and min(c for c in np.bincount(leaves) if c) >= 8
+
+
+def test_root_split_weighs_rows_by_their_programs_length_hand_worked(T):
+    """Multi-statement programs: the curvature of a row is the number of rows of its program,
+    not 1.  Worked by hand (lambda = 0, s = 0 so g = -y on every row of the program):
+
+        program   rows (x)   y    per row (g, h)
+        0         1          1    (-1, 1)
+        1         2, 1      -1    (+1, 2), (+1, 2)
+        2         3         -2    (+2, 1)
+
+    G = 3, H = 6.  Cut x < 2: left = {x=1 rows} GL = 0, HL = 3; right GR = 3, HR = 3:
+    gain = 0 + 9/3 - 9/6 = 3/2.  Cut x < 3: GL = 1, HL = 5; GR = 2, HR = 1:
+    gain = 1/5 + 4 - 3/2 = 27/10.  So the root splits at 3 with leaves -1/5 and -2.
+    Counting rows instead of curvature (h = 1: H = 4) would give 9/4 for the cut at 2 and
+    25/12 for the cut at 3 and so split at 2 with leaves 0 and -3/2."""
+    X = np.array([[1], [2], [1], [3]], np.float32)
+    off = np.array([0, 1, 3, 4], np.int32)
+    y = np.array([1, -1, -2], np.float32)
+    r = T.train(X, off, y, *all_cuts(X), n_rounds=1, max_depth=1, eta=1.0, lam=0.0)
+    assert r.split_feature.tolist() == [0, -1, -1]
+    assert r.threshold[0] == np.float32(3.0)
+    assert r.value[1] == np.float32(float(Fraction(-1, 5))) and r.value[2] == np.float32(-2.0)
+    # the two hand-worked gains really order the other way round under row counting
+    assert Fraction(27, 10) > Fraction(3, 2) and Fraction(9, 4) > Fraction(25, 12)
+
+
+def test_root_split_with_multi_statement_programs_minimises_the_weighted_objective(T):
+    """As the single-statement pin above, with programs of 1..4 rows: every row of program p
+    carries g = -y_p and curvature h = rows of p, and the objective of a leaf with weight w is
+    sum_r (g_r w + h_r w^2 / 2) + lambda w^2 / 2, minimised numerically."""
+    rng = np.random.default_rng(9)
+    for trial in range(6):
+        lens = rng.integers(1, 5, size=8)
+        off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        n = int(off[-1])
+        X = rng.integers(0, 5, size=(n, 2)).astype(np.float32)
+        y = (rng.integers(-32, 32, 8) / 4.0).astype(np.float32)
+        lam = float(rng.choice([0.0, 0.5, 2.0]))
+        co, cuts = all_cuts(X)
+        r = T.train(X, off, y, co, cuts, n_rounds=1, max_depth=1, eta=1.0, lam=lam, min_gain=-1e30)
+        g = np.repeat(-y.astype(np.float64), lens)
+        h = np.repeat(lens.astype(np.float64), lens)
+
+        def best_obj(mask):
+            gs, hs = g[mask], h[mask]
+            f = lambda w: float(np.sum(gs * w + 0.5 * hs * w * w) + 0.5 * lam * w * w)
+            return minimize_scalar(f, bounds=(-100, 100), method="bounded",
+                                   options={"xatol": 1e-12}).fun
+
+        parent = best_obj(np.ones(n, bool))
+        best = (None, None, -np.inf)
+        for f in range(2):
+            for c in cuts[co[f]:co[f + 1]]:
+                L = X[:, f] < c
+                if L.sum() == 0 or (~L).sum() == 0:
+                    continue
+                drop = parent - best_obj(L) - best_obj(~L)
+                if drop > best[2] + 1e-9:
+                    best = (f, float(c), drop)
+        assert r.split_feature[0] == best[0] and float(r.threshold[0]) == best[1]
+
+
+def test_gradients_beyond_the_fixed_point_range_are_clamped_hand_worked(T):
+    """Fixed-point gradients q = rint(g * 2^20) are clamped to +-2147483520 (= 2^31 - 128, the
+    largest float below 2^31).  One row per program, a single leaf (depth 0), bias 0, so
+    g = -y and H = number of programs.  Worked by hand:
+
+      y = -4096:  g * 2^20 = 2^32 -> q = 2147483520; eta = 1, lambda = 1:
+                  value = -(2147483520 / 2^20) / (1 + 1) = -(1024 - 2^-14)   (not -2048)
+      y = +4096:  the mirror image, +(1024 - 2^-14)
+      y = (-4096, -8192, 3), eta = 1/2, lambda = 1:  q = 2147483520, 2147483520, -3 * 2^20;
+                  G / 2^20 = 2 * (2048 - 2^-13) - 3 = 4093 - 2^-12;
+                  value = -(4093 - 2^-12) / 2 / (3 + 1) = -(511.625 - 2^-15)
+    All three values are exact in float32."""
+    X1 = np.zeros((1, 1), np.float32)
+    for yv, exp in ((-4096.0, -(1024.0 - 2.0 ** -14)), (4096.0, 1024.0 - 2.0 ** -14)):
+        r = T.train(X1, one_per_program(1), np.array([yv], np.float32), *all_cuts(X1), n_rounds=1,
+                    max_depth=0, eta=1.0, lam=1.0)
+        assert r.value.tolist() == [exp] and r.value.dtype == np.float32
+    X3 = np.zeros((3, 1), np.float32)
+    r = T.train(X3, one_per_program(3), np.array([-4096.0, -8192.0, 3.0], np.float32),
+                *all_cuts(X3), n_rounds=1, max_depth=0, eta=0.5, lam=1.0)
+    assert r.value.tolist() == [-(511.625 - 2.0 ** -15)]
+    # just inside the range nothing is clamped: y = -2047 -> q = 2047 * 2^20, value = -2047 / 2
+    r = T.train(X1, one_per_program(1), np.array([-2047.0], np.float32), *all_cuts(X1), n_rounds=1,
+                max_depth=0, eta=1.0, lam=1.0)
+    assert r.value.tolist() == [-1023.5]
