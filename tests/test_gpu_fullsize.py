@@ -1,10 +1,12 @@
-"""Parity at the full sizes of the five workloads, in the launch configuration the benchmark
-times (column-blocked features, no optional outputs).  Where scoring every program with the
-CPU oracle takes too long, a seeded sample of programs is scored one by one; the top-k cut
-is always checked in full against the oracle's cut of the device's own scores, and against
-the oracle end to end where the oracle scores everything.
+"""Parity at the full sizes of the workloads, in the launch configuration the benchmark times
+(column-blocked features, no optional outputs): every program of every family is scored by the
+CPU oracle and compared bit for bit, and the device's cut is compared with the oracle's cut of
+the oracle's own scores.  A second pass asks the library for the leaf reached by every
+(row, tree) -- at the full tree counts, all rows, first and last tile included -- and compares
+every id with the oracle's.  (configs[0] is covered the same way in test_gpu_parity.py.)
 """
 import os
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import pytest
@@ -14,6 +16,7 @@ from paper_2201_00194_amd import workloads as W
 pytestmark = pytest.mark.gpu
 RTOL, ATOL = 1e-5, 1e-6
 THREADS = min(16, os.cpu_count() or 1)
+LEAF_BLOCK_ROWS = 1 << 17          # rows per leaf-id pass (a multiple of the 64-row tile)
 
 
 @pytest.fixture(scope="module")
@@ -33,92 +36,83 @@ def run_case(api, case):
     return devs
 
 
-def check_cut_properties(oracle, fam, dev):
-    """Checks of the cut that hold at any size."""
-    own = dev.prog_score.cpu().numpy()[: fam.n_programs]
-    gi = dev.topk_idx.cpu().numpy()[: fam.k]
-    gv = dev.topk_score.cpu().numpy()[: fam.k]
-    idx, val = oracle.topk(own, fam.k)                   # oracle's cut of the device's scores
-    assert np.array_equal(gi, idx)
-    assert np.array_equal(gv.view(np.uint32), val.view(np.uint32))
-    kk = min(fam.k, fam.n_programs)
-    assert len(set(gi[:kk].tolist())) == kk
-    assert np.all(np.diff(gv[:kk]) <= 0)                 # best first
-    if kk < fam.n_programs:
-        rest = np.ones(fam.n_programs, bool)
-        rest[gi[:kk]] = False
-        assert own[rest].max() <= gv[kk - 1]             # nothing better was left out
-    return own
-
-
-def check_sample(oracle, fam, own, n_sample, seed):
-    rng = np.random.default_rng(seed)
-    n = min(n_sample, fam.n_programs)
-    sample = np.unique(np.concatenate([rng.integers(0, fam.n_programs, n),
-                                       [0, fam.n_programs - 1]]))
-    exp = oracle.score_program_sample(fam.model, fam.features, fam.prog_off, sample)
-    np.testing.assert_allclose(own[sample], exp, rtol=RTOL, atol=ATOL)
-    assert np.array_equal(own[sample].view(np.uint32), exp.view(np.uint32))
-
-
-def check_full(oracle, fam, dev):
+def check_every_program(oracle, fam, dev):
+    """Program scores and the cut against the oracle end to end; returns the oracle's scores."""
     ps = oracle.score_programs(fam.model, fam.features, fam.prog_off, threads=THREADS)
     own = dev.prog_score.cpu().numpy()[: fam.n_programs]
     np.testing.assert_allclose(own, ps, rtol=RTOL, atol=ATOL)
     assert np.array_equal(own.view(np.uint32), ps.view(np.uint32))
-    idx, val = oracle.topk(ps, fam.k)
+    idx, val = oracle.topk(ps, fam.k)                    # the oracle's cut of the oracle's scores
     assert np.array_equal(dev.topk_idx.cpu().numpy()[: fam.k], idx)
     assert np.array_equal(dev.topk_score.cpu().numpy()[: fam.k].view(np.uint32), val.view(np.uint32))
+    return ps
 
 
-def test_cfg1_full_size_every_program(api, oracle):
-    case = W.make_case(1, seed=0)
-    assert case.n_rows == 1_280_000
+def oracle_leaves(oracle, model, X):
+    """oracle.leaf_indices over row slices on the host's threads (each row is independent)."""
+    n = X.shape[0]
+    bounds = np.linspace(0, n, 4 * THREADS + 1).astype(np.int64)
+    out = np.empty((n, model.n_trees), np.int32)
+
+    def part(i):
+        a, b = int(bounds[i]), int(bounds[i + 1])
+        if b > a:
+            out[a:b] = oracle.leaf_indices(model, X[a:b])
+
+    with ThreadPoolExecutor(max_workers=THREADS) as ex:
+        list(ex.map(part, range(len(bounds) - 1)))
+    return out
+
+
+def check_every_leaf(api, oracle, fam, dev):
+    """Leaf ids of all rows of the family at its full tree count.  The rows go through the
+    library in blocks of whole tiles (a block of a column-blocked matrix is itself one), each
+    with the verification output switched on."""
+    import torch
+    nf, nt = fam.model.n_features, fam.model.n_trees
+    for r0 in range(0, fam.n_rows, LEAF_BLOCK_ROWS):
+        nr = min(LEAF_BLOCK_ROWS, fam.n_rows - r0)
+        feats = dev.features[(r0 // 64) * nf * 64:]
+        leaf = torch.full((nr * nt,), -1, dtype=torch.int16, device=feats.device)
+        off = torch.tensor([0, nr], dtype=torch.int32, device=feats.device)
+        ps = torch.empty(1, dtype=torch.float32, device=feats.device)
+        api.fs_score_families([api.Family(dev.model, feats, api.FS_COLBLOCK64, nr, off, ps, None, leaf)])
+        got = leaf.cpu().numpy().view(np.uint16).reshape(nr, nt)
+        exp = oracle_leaves(oracle, fam.model, fam.features[r0:r0 + nr])
+        assert exp.max(initial=0) < 65536
+        assert np.array_equal(got, exp.astype(np.uint16)), "leaf ids differ in rows [%d, %d)" % (r0, r0 + nr)
+
+
+def check_whole_case(api, oracle, case):
     devs = run_case(api, case)
-    for f, d in zip(case.families, devs):
-        check_cut_properties(oracle, f, d)
-    for f, d in list(zip(case.families, devs))[:3]:      # three families end to end
-        check_full(oracle, f, d)
-    for i, (f, d) in enumerate(list(zip(case.families, devs))[3:]):
-        check_sample(oracle, f, d.prog_score.cpu().numpy()[: f.n_programs], 200, 10 + i)
+    for fam, dev in zip(case.families, devs):
+        check_every_program(oracle, fam, dev)
+    for fam, dev in zip(case.families, devs):
+        check_every_leaf(api, oracle, fam, dev)
 
 
-def test_cfg2_full_size_sampled(api, oracle):
+def test_cfg1_full_size_every_program_and_leaf(api, oracle):
+    case = W.make_case(1, seed=0)
+    assert case.n_rows == 1_280_000 and len(case.families) == 8
+    check_whole_case(api, oracle, case)
+
+
+def test_cfg2_full_size_every_program_and_leaf(api, oracle):
     case = W.make_case(2, seed=0)
     assert case.n_rows == 2_097_152 and case.families[0].k == 1024
-    devs = run_case(api, case)
-    f, d = case.families[0], devs[0]
-    own = check_cut_properties(oracle, f, d)
-    check_sample(oracle, f, own, 1500, 20)
-    # the 64 best programs, recomputed one by one, really have the scores reported
-    best = d.topk_idx.cpu().numpy()[:64].astype(np.int64)
-    exp = oracle.score_program_sample(f.model, f.features, f.prog_off, best)
-    assert np.array_equal(d.topk_score.cpu().numpy()[:64].view(np.uint32), exp.view(np.uint32))
+    check_whole_case(api, oracle, case)
 
 
-def test_cfg3_full_size_sampled(api, oracle):
+def test_cfg3_full_size_every_program_and_leaf(api, oracle):
     case = W.make_case(3, seed=0)
     assert len(case.families) == 30 and case.n_programs == 201029
-    devs = run_case(api, case)
-    for i, (f, d) in enumerate(zip(case.families, devs)):
-        own = check_cut_properties(oracle, f, d)
-        check_sample(oracle, f, own, 120, 30 + i)
-    # the smallest families end to end
-    small = sorted(range(30), key=lambda i: case.families[i].n_rows)[:6]
-    for i in small:
-        check_full(oracle, case.families[i], devs[i])
+    check_whole_case(api, oracle, case)
 
 
-def test_cfg4_full_size_every_program(api, oracle):
+def test_cfg4_full_size_every_program_and_leaf(api, oracle):
     case = W.make_case(4, seed=0)
     assert len(case.families) == 64 and case.n_rows == 2_000_000
-    devs = run_case(api, case)
-    for i, (f, d) in enumerate(zip(case.families, devs)):
-        check_cut_properties(oracle, f, d)
-        if i % 4 == 0:
-            check_full(oracle, f, d)
-        else:
-            check_sample(oracle, f, d.prog_score.cpu().numpy()[: f.n_programs], 60, 40 + i)
+    check_whole_case(api, oracle, case)
 
 
 def test_foresee_step_full_size_every_program(api, oracle):
@@ -130,5 +124,4 @@ def test_foresee_step_full_size_every_program(api, oracle):
     devs = run_case(api, case)
     assert len({id(d.model) for d in devs}) == 12        # one fs_model per family
     for fam, dev in zip(case.families, devs):
-        check_cut_properties(oracle, fam, dev)
-        check_full(oracle, fam, dev)
+        check_every_program(oracle, fam, dev)
