@@ -32,7 +32,18 @@
  * must belong to the device that is current when the call is made.  Descriptor arrays
  * (fs_family[], fs_topk_req[]) are HOST memory and are only read during the call.
  * Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream)
- * and the call returns without waiting for it.
+ * and the call normally returns without waiting for it.  fs_score_families and fs_topk
+ * block the host only in these cases:
+ *   - the library scratch of the device must grow for this call: the device is
+ *     synchronised, the old buffer freed and a larger one allocated.  A caller that has
+ *     reserved enough (fs_workspace_bytes, fs_topk_workspace_bytes, fs_workspace_reserve)
+ *     never gets here;
+ *   - the call's descriptors (about 300 bytes per family, 48 per top-k workgroup) exceed
+ *     the staging capacity (64 KB unless grown before): staging is re-allocated;
+ *   - descriptors are staged through a ring of 8 pinned slots per device; the ninth
+ *     submission waits until the first has finished on the device.
+ * fs_model_create, fs_trainer_create and the fs_trainer_* read-back calls synchronise
+ * (stated where they are declared).
  */
 #ifndef FAMILYSEER_H
 #define FAMILYSEER_H
@@ -133,10 +144,11 @@ typedef struct fs_family {
  * allowed.  Errors are detected on the host before anything is enqueued: FS_EINVAL
  * (NULL pointers, negative sizes, unknown layout, misaligned features), FS_ENOMEM /
  * FS_EDEVICE (scratch growth, launch failure).
- * The library keeps one scratch buffer per device (row scores of families that pass
+ * The library keeps one scoring scratch buffer per device (row scores of families that pass
  * row_score == NULL, rank tiles of models it rank-codes, re-tiled copies of row-major
- * input) which all calls on the device share: calls that use it -- in doubt, all calls of
- * fs_score_families and fs_topk -- must not overlap in time on different streams.
+ * input) which all fs_score_families calls on the device share: two such calls must not
+ * overlap in time on different streams.  fs_topk has a scratch region of its own, so a
+ * scoring call and a top-k call on unrelated data may overlap.
  */
 int fs_score_families(int32_t n_families, const fs_family *fams /* HOST */, void *stream);
 
@@ -157,10 +169,31 @@ typedef struct fs_topk_req {
  * index ascending) (Section 3.2: candidates are sorted by the model's estimate and the
  * top k are kept; Algorithm 1: k = g, or g*p in the foresee step).  One batched
  * submission for all requests.  Errors: FS_EINVAL, FS_EUNSUPPORTED (k > FS_MAX_TOPK),
- * FS_ENOMEM, FS_EDEVICE.  Uses library scratch shared by all calls on the device: calls
- * must not overlap in time on different streams.
+ * FS_ENOMEM, FS_EDEVICE.  Requests of 8192 entries and more use the device's top-k scratch
+ * region, which all fs_topk calls on the device share: two such calls must not overlap in
+ * time on different streams.
  */
 int fs_topk(int32_t n_requests, const fs_topk_req *reqs /* HOST */, void *stream);
+
+/* ---- library scratch ------------------------------------------------------------------- */
+
+/*
+ * Bytes of scoring scratch that fs_score_families(n_families, fams, ...) would use, and of
+ * top-k scratch that fs_topk(n_requests, reqs, ...) would use.  Only sizes, layouts, models
+ * and the NULL-ness of row_score are looked at; nothing is enqueued.  Return 0 for calls that
+ * need none, and 0 with fs_last_error() set for descriptors the scoring / top-k call itself
+ * would reject.
+ */
+size_t fs_workspace_bytes(int32_t n_families, const fs_family *fams /* HOST */);
+size_t fs_topk_workspace_bytes(int32_t n_requests, const fs_topk_req *reqs /* HOST */);
+
+/*
+ * Grow the current device's scoring and top-k scratch to at least these sizes now (either may
+ * be 0) and set up descriptor staging.  May synchronise the device and allocate.  Afterwards
+ * calls whose needs stay within the reserved sizes neither allocate nor synchronise for
+ * scratch.  Errors: FS_ENOMEM, FS_EDEVICE.
+ */
+int fs_workspace_reserve(size_t score_bytes, size_t topk_bytes);
 
 /* ---- layout helper -------------------------------------------------------------------- */
 
@@ -207,6 +240,31 @@ int fs_gather_programs(int32_t n_features, int32_t n_sources, const fs_gather_sr
                        const int32_t *keep /* DEVICE */, int32_t n_keep, float *out_features,
                        int64_t out_row_capacity, int32_t *out_prog_off, float *out_score,
                        int32_t *status, void *stream);
+
+/* ---- test and tuning hooks -------------------------------------------------------------- */
+
+/*
+ * Process-wide overrides of choices the library otherwise makes by itself.  They exist so
+ * that tests can drive every kernel form on small inputs and so that tile / chunk shapes can
+ * be swept; results never depend on them (every form is exact).  value < 0 restores the
+ * automatic choice.  The model options are read by fs_model_create (models already built keep
+ * their plan), the training options by fs_train_boost.  Nothing else -- no environment
+ * variable -- changes which kernel a model or trainer takes.
+ */
+enum {
+    FS_TUNE_LDS_TILES = 0,        /* 1..3: 64-row tiles per workgroup of the LDS-staged traversal  */
+    FS_TUNE_LDS_MODE = 1,         /* 1: half-LDS workgroups (two per compute unit), 2: full         */
+    FS_TUNE_RANK = 2,             /* 0: never rank-code a model, 1: whenever its trees allow        */
+    FS_TUNE_RANK_TILES = 3,       /* 1, 2, 3, 4 or 6: tiles per workgroup of the rank traversal     */
+    FS_TUNE_VERBOSE = 4,          /* 1: fs_model_create reports its plan on stderr                  */
+    FS_TUNE_TRAIN_SLAB_ROWS = 5,  /* 64..65536: rows per histogram slab                             */
+    FS_TUNE_TRAIN_SORT = 6,       /* 0: never regroup rows by node, 1: whenever possible            */
+    FS_TUNE_TRAIN_PACKED = 7,     /* 0: separate 64-bit gradient / curvature sums only              */
+    FS_TUNE_LDS_PHASES = 8,       /* 0: one lock-step walk to the deepest level; 1: phased walk     */
+    FS_TUNE_OPTIONS = 9
+};
+int fs_tune_set(int32_t option, int32_t value);
+int32_t fs_tune_get(int32_t option);   /* current override, -1 = automatic */
 
 /* ---- per-kernel timing (measurement aid) ----------------------------------------------------- */
 

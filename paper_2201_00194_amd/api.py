@@ -72,6 +72,19 @@ _lib.fs_colblock64_floats.restype = ctypes.c_int64
 _lib.fs_colblock64_floats.argtypes = [ctypes.c_int64, ctypes.c_int32]
 
 
+_lib.fs_workspace_bytes.restype = ctypes.c_size_t
+_lib.fs_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.POINTER(_FsFamily)]
+_lib.fs_topk_workspace_bytes.restype = ctypes.c_size_t
+_lib.fs_topk_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.POINTER(_FsTopkReq)]
+_lib.fs_workspace_reserve.restype = ctypes.c_int
+_lib.fs_workspace_reserve.argtypes = [ctypes.c_size_t, ctypes.c_size_t]
+_lib.fs_tune_set.restype = ctypes.c_int
+_lib.fs_tune_set.argtypes = [ctypes.c_int32, ctypes.c_int32]
+_lib.fs_tune_get.restype = ctypes.c_int32
+_lib.fs_tune_get.argtypes = [ctypes.c_int32]
+(FS_TUNE_LDS_TILES, FS_TUNE_LDS_MODE, FS_TUNE_RANK, FS_TUNE_RANK_TILES, FS_TUNE_VERBOSE,
+ FS_TUNE_TRAIN_SLAB_ROWS, FS_TUNE_TRAIN_SORT, FS_TUNE_TRAIN_PACKED, FS_TUNE_LDS_PHASES) = range(9)
+
 _lib.fs_profile_begin.restype = ctypes.c_int
 _lib.fs_profile_begin.argtypes = [ctypes.c_int32]
 _lib.fs_profile_end.restype = ctypes.c_int
@@ -209,6 +222,30 @@ def fs_topk(reqs, stream: Optional[torch.cuda.Stream] = None) -> None:
     if not isinstance(reqs, PreparedTopk):
         reqs = PreparedTopk(reqs)
     _check(_lib.fs_topk(reqs.n, reqs.arr, _stream_ptr(stream)))
+
+
+def fs_workspace_bytes(fams) -> int:
+    if not isinstance(fams, PreparedFamilies):
+        fams = PreparedFamilies(fams)
+    return int(_lib.fs_workspace_bytes(fams.n, fams.arr))
+
+
+def fs_topk_workspace_bytes(reqs) -> int:
+    if not isinstance(reqs, PreparedTopk):
+        reqs = PreparedTopk(reqs)
+    return int(_lib.fs_topk_workspace_bytes(reqs.n, reqs.arr))
+
+
+def fs_workspace_reserve(score_bytes: int, topk_bytes: int) -> None:
+    _check(_lib.fs_workspace_reserve(int(score_bytes), int(topk_bytes)))
+
+
+def fs_tune_set(option: int, value: int) -> None:
+    _check(_lib.fs_tune_set(int(option), int(value)))
+
+
+def fs_tune_get(option: int) -> int:
+    return int(_lib.fs_tune_get(int(option)))
 
 
 def fs_colblock64_floats(n_rows: int, n_features: int) -> int:

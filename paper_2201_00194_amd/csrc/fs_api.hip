@@ -34,6 +34,7 @@ int fail_hip(hipError_t e, const char *what)
 // ---- per-device state: descriptor ring and scratch ---------------------------------------------
 constexpr int kSlots = 8;
 constexpr int kMaxDevices = 16;
+constexpr size_t kSlotBytes = 65536;   // descriptor staging a slot starts with
 
 struct Slot {
     void *d_buf = nullptr;
@@ -43,11 +44,14 @@ struct Slot {
     bool used = false;
 };
 
+// Two scratch regions per device, so that a scoring call and a top-k call never share bytes.
+enum { kScratchScore = 0, kScratchTopk = 1, kScratchRegions = 2 };
+
 struct DeviceCtx {
     Slot slots[kSlots];
     int next = 0;
-    float *scratch = nullptr;
-    size_t scratch_floats = 0;
+    float *scratch[kScratchRegions] = {nullptr, nullptr};
+    size_t scratch_floats[kScratchRegions] = {0, 0};
 };
 
 static std::mutex g_mu;
@@ -75,7 +79,7 @@ static int acquire_slot(DeviceCtx *ctx, size_t bytes, Slot **out)
     if (s->used)
         FS_HIP(hipEventSynchronize(s->done));
     if (s->cap < bytes) {
-        size_t cap = bytes < 4096 ? 4096 : bytes * 2;
+        size_t cap = bytes < kSlotBytes ? kSlotBytes : bytes * 2;
         if (s->d_buf)
             FS_HIP(hipFree(s->d_buf));
         if (s->h_buf)
@@ -90,20 +94,32 @@ static int acquire_slot(DeviceCtx *ctx, size_t bytes, Slot **out)
     return FS_OK;
 }
 
-static int ensure_scratch(DeviceCtx *ctx, size_t floats)
+// Region `which` with room for `floats`; `exact` reserves just that (fs_workspace_reserve),
+// otherwise a quarter more so that slowly growing calls do not re-allocate every time.
+static int ensure_scratch(DeviceCtx *ctx, int which, size_t floats, bool exact = false)
 {
-    if (ctx->scratch_floats >= floats)
+    if (ctx->scratch_floats[which] >= floats)
         return FS_OK;
     // Earlier submissions may still read the old buffer.
     FS_HIP(hipDeviceSynchronize());
-    if (ctx->scratch)
-        FS_HIP(hipFree(ctx->scratch));
-    ctx->scratch = nullptr;
-    ctx->scratch_floats = 0;
-    size_t want = floats + floats / 4 + 1024;
-    FS_HIP(hipMalloc((void **)&ctx->scratch, want * sizeof(float)));
-    ctx->scratch_floats = want;
+    if (ctx->scratch[which])
+        FS_HIP(hipFree(ctx->scratch[which]));
+    ctx->scratch[which] = nullptr;
+    ctx->scratch_floats[which] = 0;
+    size_t want = exact ? floats : floats + floats / 4 + 1024;
+    FS_HIP(hipMalloc((void **)&ctx->scratch[which], want * sizeof(float)));
+    ctx->scratch_floats[which] = want;
     return FS_OK;
+}
+
+// ---- test and tuning overrides -----------------------------------------------------------------
+static std::mutex g_tune_mu;
+static int g_tune[FS_TUNE_OPTIONS] = {-1, -1, -1, -1, -1, -1, -1, -1, -1};
+
+int tune(int option)
+{
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    return option >= 0 && option < FS_TUNE_OPTIONS ? g_tune[option] : -1;
 }
 
 // ---- optional per-kernel timing -------------------------------------------------------------
@@ -193,7 +209,18 @@ extern "C" int fs_profile_end(double *ms_by_kernel, int32_t *launches_by_kernel)
 
 // ---- small entry points ------------------------------------------------------------------------
 extern "C" const char *fs_last_error(void) { return fs::g_err; }
-extern "C" int fs_version(void) { return 100; }
+extern "C" int fs_version(void) { return 200; }
+
+extern "C" int fs_tune_set(int32_t option, int32_t value)
+{
+    if (option < 0 || option >= FS_TUNE_OPTIONS)
+        return fail(FS_EINVAL, "fs_tune_set: unknown option %d", option);
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    g_tune[option] = value < 0 ? -1 : value;
+    return FS_OK;
+}
+
+extern "C" int32_t fs_tune_get(int32_t option) { return tune(option); }
 
 extern "C" int64_t fs_colblock64_floats(int64_t n_rows, int32_t n_features)
 {
@@ -214,6 +241,85 @@ static bool rowmajor_in_kernel(const fs_model *m)
     return m->lds_ok && m->n_features % 4 == 0 && m->lds_tile0 >= 8 * (m->n_features + 1) * 4;
 }
 
+// Validates the family descriptors (everything that does not need the device) and adds up the
+// scoring scratch the call uses, in floats.  `dev` < 0: the models' device is not checked.
+static int score_scratch_floats(const char *who, int32_t n_families, const fs_family *fams, int dev,
+                                size_t *out)
+{
+    size_t scratch_floats = 0;
+    for (int f = 0; f < n_families; ++f) {
+        const fs_family &a = fams[f];
+        if (!a.model)
+            return fail(FS_EINVAL, "%s: family %d has no model", who, f);
+        if (dev >= 0 && a.model->device != dev)
+            return fail(FS_EINVAL, "%s: family %d: model lives on device %d, "
+                        "current device is %d", who, f, a.model->device, dev);
+        if (a.n_rows < 0 || a.n_rows >= ((int64_t)1 << 31))
+            return fail(FS_EINVAL, "%s: family %d: n_rows %lld outside [0, 2^31)", who, f,
+                        (long long)a.n_rows);
+        if (a.n_programs < 0)
+            return fail(FS_EINVAL, "%s: family %d: n_programs is negative", who, f);
+        if (a.layout != FS_ROWMAJOR && a.layout != FS_COLBLOCK64)
+            return fail(FS_EINVAL, "%s: family %d: unknown layout %d", who, f, a.layout);
+        if (a.n_rows > 0 && !a.features)
+            return fail(FS_EINVAL, "%s: family %d: features is NULL", who, f);
+        if (((uintptr_t)a.features & 15) != 0)
+            return fail(FS_EINVAL, "%s: family %d: features not 16-byte aligned", who, f);
+        if (a.n_programs > 0 && !a.prog_off)
+            return fail(FS_EINVAL, "%s: family %d: prog_off is NULL", who, f);
+        if (a.n_programs > 0 && !a.prog_score)
+            return fail(FS_EINVAL, "%s: family %d: prog_score is NULL", who, f);
+        if (a.n_programs == 0 && a.n_rows != 0)
+            return fail(FS_EINVAL, "%s: family %d: %lld rows but no programs", who, f,
+                        (long long)a.n_rows);
+        if (!a.row_score)
+            scratch_floats += (size_t)a.n_rows;
+        if (a.model->rank_ok)                                // u16 rank tiles, in float units
+            scratch_floats += (size_t)((a.n_rows + 63) / 64) * 32 * (size_t)rank_tile_cols(a.model->n_features) + 4;
+        if ((a.model->rank_ok || a.model->lds_ok) && a.layout == FS_ROWMAJOR &&
+            !rowmajor_in_kernel(a.model))                                         // re-tiled copy
+            scratch_floats += (size_t)((a.n_rows + 63) / 64) * 64 * (size_t)a.model->n_features + 4;
+    }
+    *out = scratch_floats;
+    return FS_OK;
+}
+
+extern "C" size_t fs_workspace_bytes(int32_t n_families, const fs_family *fams)
+{
+    if (n_families <= 0 || !fams) {
+        if (n_families < 0 || (n_families > 0 && !fams))
+            (void)fail(FS_EINVAL, "fs_workspace_bytes: bad arguments");
+        return 0;
+    }
+    size_t floats = 0;
+    if (score_scratch_floats("fs_workspace_bytes", n_families, fams, -1, &floats) != FS_OK)
+        return 0;
+    return floats * sizeof(float);
+}
+
+extern "C" int fs_workspace_reserve(size_t score_bytes, size_t topk_bytes)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx *ctx = nullptr;
+    int rc = current_ctx(&ctx);
+    if (rc != FS_OK)
+        return rc;
+    rc = ensure_scratch(ctx, kScratchScore, (score_bytes + 3) / 4, true);
+    if (rc == FS_OK)
+        rc = ensure_scratch(ctx, kScratchTopk, (topk_bytes + 3) / 4, true);
+    for (int i = 0; i < kSlots && rc == FS_OK; ++i) {       // staging of every slot of the ring
+        Slot *s = &ctx->slots[i];
+        if (!s->done)
+            FS_HIP(hipEventCreateWithFlags(&s->done, hipEventDisableTiming));
+        if (s->cap == 0) {
+            FS_HIP(hipMalloc(&s->d_buf, kSlotBytes));
+            FS_HIP(hipHostMalloc(&s->h_buf, kSlotBytes, hipHostMallocDefault));
+            s->cap = kSlotBytes;
+        }
+    }
+    return rc;
+}
+
 extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void *stream_)
 {
     hipStream_t stream = (hipStream_t)stream_;
@@ -232,40 +338,10 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         return rc;
 
     size_t scratch_floats = 0;
-    for (int f = 0; f < n_families; ++f) {
-        const fs_family &a = fams[f];
-        if (!a.model)
-            return fail(FS_EINVAL, "fs_score_families: family %d has no model", f);
-        if (a.model->device != dev)
-            return fail(FS_EINVAL, "fs_score_families: family %d: model lives on device %d, "
-                        "current device is %d", f, a.model->device, dev);
-        if (a.n_rows < 0 || a.n_rows >= ((int64_t)1 << 31))
-            return fail(FS_EINVAL, "fs_score_families: family %d: n_rows %lld outside [0, 2^31)", f,
-                        (long long)a.n_rows);
-        if (a.n_programs < 0)
-            return fail(FS_EINVAL, "fs_score_families: family %d: n_programs is negative", f);
-        if (a.layout != FS_ROWMAJOR && a.layout != FS_COLBLOCK64)
-            return fail(FS_EINVAL, "fs_score_families: family %d: unknown layout %d", f, a.layout);
-        if (a.n_rows > 0 && !a.features)
-            return fail(FS_EINVAL, "fs_score_families: family %d: features is NULL", f);
-        if (((uintptr_t)a.features & 15) != 0)
-            return fail(FS_EINVAL, "fs_score_families: family %d: features not 16-byte aligned", f);
-        if (a.n_programs > 0 && !a.prog_off)
-            return fail(FS_EINVAL, "fs_score_families: family %d: prog_off is NULL", f);
-        if (a.n_programs > 0 && !a.prog_score)
-            return fail(FS_EINVAL, "fs_score_families: family %d: prog_score is NULL", f);
-        if (a.n_programs == 0 && a.n_rows != 0)
-            return fail(FS_EINVAL, "fs_score_families: family %d: %lld rows but no programs", f,
-                        (long long)a.n_rows);
-        if (!a.row_score)
-            scratch_floats += (size_t)a.n_rows;
-        if (a.model->rank_ok)                                // u16 rank tiles, in float units
-            scratch_floats += (size_t)((a.n_rows + 63) / 64) * 32 * (size_t)rank_tile_cols(a.model->n_features) + 4;
-        if ((a.model->rank_ok || a.model->lds_ok) && a.layout == FS_ROWMAJOR &&
-            !rowmajor_in_kernel(a.model))                                         // re-tiled copy
-            scratch_floats += (size_t)((a.n_rows + 63) / 64) * 64 * (size_t)a.model->n_features + 4;
-    }
-    rc = ensure_scratch(ctx, scratch_floats);
+    rc = score_scratch_floats("fs_score_families", n_families, fams, dev, &scratch_floats);
+    if (rc != FS_OK)
+        return rc;
+    rc = ensure_scratch(ctx, kScratchScore, scratch_floats);
     if (rc != FS_OK)
         return rc;
 
@@ -290,7 +366,7 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         if (a.row_score) {
             d.row_score = a.row_score;
         } else {
-            d.row_score = ctx->scratch + scratch_pos;
+            d.row_score = ctx->scratch[kScratchScore] + scratch_pos;
             scratch_pos += (size_t)a.n_rows;
         }
         d.leaf_idx = a.leaf_idx;
@@ -323,7 +399,7 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
             const int64_t tiles = (a.n_rows + 63) / 64;
             scratch_pos = (scratch_pos + 3) & ~(size_t)3;
             d.rowmajor_src = a.features;
-            d.features = ctx->scratch + scratch_pos;
+            d.features = ctx->scratch[kScratchScore] + scratch_pos;
             d.layout = FS_COLBLOCK64;
             scratch_pos += (size_t)tiles * 64 * (size_t)a.model->n_features;
             d.retile_colblocks = (a.model->n_features + 127) / 128;
@@ -352,7 +428,7 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         if (a.model->rank_ok && (colblock || in_kernel)) {
             const int64_t tiles = (a.n_rows + 63) / 64;
             scratch_pos = (scratch_pos + 3) & ~(size_t)3;            // 16-byte aligned tiles
-            d.ranks = (uint16_t *)(ctx->scratch + scratch_pos);
+            d.ranks = (uint16_t *)(ctx->scratch[kScratchScore] + scratch_pos);
             scratch_pos += (size_t)tiles * 32 * (size_t)rank_tile_cols(a.model->n_features);
             const int len = 1 << a.model->cut_bits;
             int per_group = kBinTableBytes / 4 / len;
@@ -431,6 +507,76 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
 }
 
 // ---- top-k -------------------------------------------------------------------------------------
+struct TopkSizes {
+    size_t n_blocks = 0, n_merge = 0, comp_total = 0, n_pairs_total = 0;
+    int max_comp = 0, n_levels = 0, max_k = 0;
+};
+
+// Validates the requests and sizes the submission: first-stage workgroups, LDS merges, pairwise
+// merges per level, scratch composites (8 bytes each).
+static int topk_sizes(const char *who, int32_t n_requests, const fs_topk_req *reqs, TopkSizes *out)
+{
+    TopkSizes z;
+    for (int i = 0; i < n_requests; ++i) {
+        const fs_topk_req &r = reqs[i];
+        if (r.n < 0 || r.k < 0)
+            return fail(FS_EINVAL, "%s: request %d: n=%d k=%d must be non-negative", who, i, r.n, r.k);
+        if (r.k > FS_MAX_TOPK)
+            return fail(FS_EUNSUPPORTED, "%s: request %d: k=%d exceeds FS_MAX_TOPK=%d", who, i, r.k,
+                        FS_MAX_TOPK);
+        if (r.n > 0 && !r.score)
+            return fail(FS_EINVAL, "%s: request %d: score is NULL", who, i);
+        if (r.k > 0 && !r.out_idx)
+            return fail(FS_EINVAL, "%s: request %d: out_idx is NULL", who, i);
+        if (r.k > z.max_k)
+            z.max_k = r.k;
+    }
+    for (int i = 0; i < n_requests; ++i) {
+        const fs_topk_req &r = reqs[i];
+        const TopkPlan p = topk_plan(r.n, r.k);
+        z.n_blocks += (size_t)p.s;
+        if (p.mode == 1) {
+            ++z.n_merge;
+            z.comp_total += (size_t)p.s * (size_t)r.k;
+            int kp = 1;
+            while (kp < r.k)
+                kp <<= 1;
+            if (p.s * kp > z.max_comp)
+                z.max_comp = p.s * kp;
+        } else if (p.mode == 2) {
+            // first-stage lists: min(k, length) per slice
+            const size_t every = (size_t)r.n, capped = (size_t)p.s * (size_t)r.k;
+            z.comp_total += every < capped ? every : capped;
+            int lists = p.s, levels = 0;
+            while (lists > 1) {
+                const int pairs = lists / 2;
+                z.n_pairs_total += (size_t)pairs;
+                if (lists > 2)
+                    z.comp_total += (size_t)pairs * (size_t)r.k;   // merged lists (the last level writes the answer)
+                lists = pairs + (lists & 1);
+                ++levels;
+            }
+            if (levels > z.n_levels)
+                z.n_levels = levels;
+        }
+    }
+    *out = z;
+    return FS_OK;
+}
+
+extern "C" size_t fs_topk_workspace_bytes(int32_t n_requests, const fs_topk_req *reqs)
+{
+    if (n_requests <= 0 || !reqs) {
+        if (n_requests < 0 || (n_requests > 0 && !reqs))
+            (void)fail(FS_EINVAL, "fs_topk_workspace_bytes: bad arguments");
+        return 0;
+    }
+    TopkSizes z;
+    if (topk_sizes("fs_topk_workspace_bytes", n_requests, reqs, &z) != FS_OK)
+        return 0;
+    return z.comp_total * sizeof(unsigned long long);
+}
+
 extern "C" int fs_topk(int32_t n_requests, const fs_topk_req *reqs, void *stream_)
 {
     hipStream_t stream = (hipStream_t)stream_;
@@ -440,100 +586,26 @@ extern "C" int fs_topk(int32_t n_requests, const fs_topk_req *reqs, void *stream
         return FS_OK;
     if (!reqs)
         return fail(FS_EINVAL, "fs_topk: reqs is NULL");
-    int max_k = 0;
-    for (int i = 0; i < n_requests; ++i) {
-        const fs_topk_req &r = reqs[i];
-        if (r.n < 0 || r.k < 0)
-            return fail(FS_EINVAL, "fs_topk: request %d: n=%d k=%d must be non-negative", i, r.n, r.k);
-        if (r.k > FS_MAX_TOPK)
-            return fail(FS_EUNSUPPORTED, "fs_topk: request %d: k=%d exceeds FS_MAX_TOPK=%d", i, r.k,
-                        FS_MAX_TOPK);
-        if (r.n > 0 && !r.score)
-            return fail(FS_EINVAL, "fs_topk: request %d: score is NULL", i);
-        if (r.k > 0 && !r.out_idx)
-            return fail(FS_EINVAL, "fs_topk: request %d: out_idx is NULL", i);
-        if (r.k > max_k)
-            max_k = r.k;
-    }
+    TopkSizes z;
+    int rc = topk_sizes("fs_topk", n_requests, reqs, &z);
+    if (rc != FS_OK)
+        return rc;
+    const int max_k = z.max_k;
     if (max_k == 0)
         return FS_OK;
 
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceCtx *ctx = nullptr;
-    int rc = current_ctx(&ctx);
+    rc = current_ctx(&ctx);
     if (rc != FS_OK)
         return rc;
-    // Three ways to serve a request:
-    //   0  one workgroup, finished by the first kernel;
-    //   1  long request, k <= 4096: slices (one workgroup each) leave their best k in scratch and
-    //      one workgroup merges them in LDS;
-    //   2  long request with a wider cut: slices of about kTopkWideSlice entries leave their best
-    //      min(k, length) sorted, then pairwise merges in global memory, level by level.
-    struct Plan { int mode, s, per; };
-    auto plan_of = [](const fs_topk_req &r) {
-        Plan p = {0, 1, r.n};
-        if (r.n < kTopkSliceMin || r.k == 0)
-            return p;
-        int kp = 1;
-        while (kp < r.k)
-            kp <<= 1;
-        if (kp > kTopkMergeCap / 4) {
-            int s = (r.n + kTopkWideSlice - 1) / kTopkWideSlice;
-            if (s > kTopkWideMaxSlices)
-                s = kTopkWideMaxSlices;
-            if (s >= 2) {
-                p.mode = 2;
-                p.s = s;
-                p.per = (((r.n + s - 1) / s) + 63) & ~63;
-            }
-            return p;
-        }
-        int s = kTopkMergeCap / kp;
-        if (s > kTopkMaxSlices)
-            s = kTopkMaxSlices;
-        if (s > r.n / kTopkSliceEntries)
-            s = r.n / kTopkSliceEntries;
-        if (s >= 2) {
-            p.mode = 1;
-            p.s = s;
-            p.per = (((r.n + s - 1) / s) + 63) & ~63;
-        }
-        return p;
-    };
-    // sizes: first-stage workgroups, LDS merges, merge-path pairs per level, scratch composites
-    size_t n_blocks = 0, n_merge = 0, comp_total = 0, n_pairs_total = 0;
-    int max_comp = 0, n_levels = 0;
-    for (int i = 0; i < n_requests; ++i) {
-        const fs_topk_req &r = reqs[i];
-        const Plan p = plan_of(r);
-        n_blocks += (size_t)p.s;
-        if (p.mode == 1) {
-            ++n_merge;
-            comp_total += (size_t)p.s * (size_t)r.k;
-            int kp = 1;
-            while (kp < r.k)
-                kp <<= 1;
-            if (p.s * kp > max_comp)
-                max_comp = p.s * kp;
-        } else if (p.mode == 2) {
-            // first-stage lists: min(k, length) per slice
-            const size_t every = (size_t)r.n, capped = (size_t)p.s * (size_t)r.k;
-            comp_total += every < capped ? every : capped;
-            int lists = p.s, levels = 0;
-            while (lists > 1) {
-                const int pairs = lists / 2;
-                n_pairs_total += (size_t)pairs;
-                if (lists > 2)
-                    comp_total += (size_t)pairs * (size_t)r.k;   // merged lists (the last level writes the answer)
-                lists = pairs + (lists & 1);
-                ++levels;
-            }
-            if (levels > n_levels)
-                n_levels = levels;
-        }
-    }
+    auto plan_of = [](const fs_topk_req &r) { return topk_plan(r.n, r.k); };
+    typedef TopkPlan Plan;
+    const size_t n_blocks = z.n_blocks, n_merge = z.n_merge, comp_total = z.comp_total,
+                 n_pairs_total = z.n_pairs_total;
+    const int max_comp = z.max_comp, n_levels = z.n_levels;
     if (comp_total) {
-        rc = ensure_scratch(ctx, comp_total * 2);
+        rc = ensure_scratch(ctx, kScratchTopk, comp_total * 2);
         if (rc != FS_OK)
             return rc;
     }
@@ -548,7 +620,7 @@ extern "C" int fs_topk(int32_t n_requests, const fs_topk_req *reqs, void *stream
     TopkDesc *h = (TopkDesc *)slot->h_buf;
     TopkMergeDesc *hm = (TopkMergeDesc *)((char *)slot->h_buf + merge_off);
     TopkPairDesc *hp = (TopkPairDesc *)((char *)slot->h_buf + path_off);
-    unsigned long long *comp = (unsigned long long *)ctx->scratch;
+    unsigned long long *comp = (unsigned long long *)ctx->scratch[kScratchTopk];
     // merge-path descriptors are stored level by level: first count the pairs of every level
     constexpr int kMaxLevels = 8;
     size_t level_pairs[kMaxLevels] = {0}, level_at[kMaxLevels] = {0};
@@ -646,7 +718,7 @@ extern "C" int fs_topk(int32_t n_requests, const fs_topk_req *reqs, void *stream
             }
         }
     }
-    if ((size_t)(comp - (unsigned long long *)ctx->scratch) > comp_total || b != n_blocks || m != n_merge)
+    if ((size_t)(comp - (unsigned long long *)ctx->scratch[kScratchTopk]) > comp_total || b != n_blocks || m != n_merge)
         return fail(FS_EDEVICE, "fs_topk: internal plan mismatch");
     FS_HIP(hipMemcpyAsync(slot->d_buf, slot->h_buf, total_bytes, hipMemcpyHostToDevice, stream));
     slot->used = true;

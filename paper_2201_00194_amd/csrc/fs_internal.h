@@ -20,6 +20,9 @@ int fail_hip(hipError_t e, const char *what);
             return ::fs::fail_hip(fs_e_, #call);       \
     } while (0)
 
+// ---- test and tuning overrides (fs_tune_set); -1 = automatic ---------------------------------
+int tune(int option);
+
 // ---- device-side model formats -------------------------------------------------------------
 
 // Node of the reference device layout (global memory).  One entry per node, trees
@@ -98,9 +101,9 @@ struct fs_model {
     int32_t rk_depth;          // common depth of the trees
     int32_t rk_tiles;          // 64-row tiles per workgroup
     int32_t rk_trees_per_chunk;
-    int32_t rk_tree_bytes;     // 4 * (2^(depth+1) - 1)
+    int32_t rk_tree_bytes;     // 4 * 2^(depth+1): heap words 1 .. 2^(depth+1)-1, word 0 unused
     int32_t rk_tile0;          // LDS byte offset of the first (u16) feature tile
-    uint32_t *d_rk_nodes;      // [n_trees][2^(depth+1) - 1] heap order: splits then leaf values
+    uint32_t *d_rk_nodes;      // [n_trees][2^(depth+1)] 1-based heap order: splits then leaf values
     uint16_t *d_rk_ids;        // same shape: caller's local node id
     float *d_cuts;             // [n_features][2^cut_bits]: the feature's sorted distinct
                                // thresholds, NaN-padded, as a breadth-first search tree
@@ -218,6 +221,44 @@ constexpr int kTopkMaxSlices = 16;
 constexpr int kTopkMergeCap = 16384;     // composites (lists padded to a power of two) the merge holds in LDS
 constexpr int kTopkWideSlice = 2048;     // slice length of cuts too wide for the LDS merge (k > 4096)
 constexpr int kTopkWideMaxSlices = 128;
+// How a top-k request of n entries and cut k is served:
+//   mode 0  one workgroup, finished by the first kernel;
+//   mode 1  long request, k <= 4096: `s` slices of `per` entries (one workgroup each) leave their
+//           best k in scratch and one workgroup merges them in LDS;
+//   mode 2  long request with a wider cut: slices of about kTopkWideSlice entries leave their best
+//           min(k, length) sorted, then pairwise merges in global memory, level by level.
+struct TopkPlan { int mode, s, per; };
+inline TopkPlan topk_plan(int n, int k)
+{
+    TopkPlan p = {0, 1, n};
+    if (n < kTopkSliceMin || k == 0)
+        return p;
+    int kp = 1;
+    while (kp < k)
+        kp <<= 1;
+    if (kp > kTopkMergeCap / 4) {
+        int s = (n + kTopkWideSlice - 1) / kTopkWideSlice;
+        if (s > kTopkWideMaxSlices)
+            s = kTopkWideMaxSlices;
+        if (s >= 2) {
+            p.mode = 2;
+            p.s = s;
+            p.per = (((n + s - 1) / s) + 63) & ~63;
+        }
+        return p;
+    }
+    int s = kTopkMergeCap / kp;
+    if (s > kTopkMaxSlices)
+        s = kTopkMaxSlices;
+    if (s > n / kTopkSliceEntries)
+        s = n / kTopkSliceEntries;
+    if (s >= 2) {
+        p.mode = 1;
+        p.s = s;
+        p.per = (((n + s - 1) / s) + 63) & ~63;
+    }
+    return p;
+}
 int launch_topk_pairs(const TopkPairDesc *d_desc, int n_pairs, int max_entries, hipStream_t stream);
 int launch_retile(const FamDesc *d_desc, int n_families, int total_blocks, hipStream_t stream);
 int launch_pack_colblock64(const float *in, int64_t n_rows, int32_t n_features, float *out,

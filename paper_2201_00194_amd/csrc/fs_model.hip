@@ -253,9 +253,7 @@ void build_rank_format(fs_model *m, int n_features, int n_trees, int depth, cons
     const size_t tree_bytes = words * 4, tile_bytes = (size_t)rank_tile_cols(n_features) * 128;
     const size_t reg_limit = (size_t)kRankPrefetchRegs * 64 * kRankWaves * 16;
     int best_t = 0, best_per = 0, best_score = -1;
-    int forced = 0;
-    if (const char *e = getenv("FS_TUNE_RANK_TILES"))
-        forced = atoi(e);
+    const int forced = tune(FS_TUNE_RANK_TILES);
     const int choices[] = {6, 4, 3, 2, 1};
     for (int nt : choices) {
         if (forced > 0 && nt != forced)
@@ -285,7 +283,7 @@ void build_rank_format(fs_model *m, int n_features, int n_trees, int depth, cons
     m->rk_tree_bytes = (int32_t)tree_bytes;
     m->rk_tile0 = kRankLdsBytes - best_t * (int32_t)tile_bytes;
     m->cut_bits = bits;
-    if (getenv("FS_TUNE_VERBOSE"))
+    if (tune(FS_TUNE_VERBOSE) > 0)
         fprintf(stderr, "fs_model_create: rank-coded depth=%d tiles=%d trees/chunk=%d max_cuts=%zu\n",
                 depth, best_t, best_per, max_cuts);
 }
@@ -423,11 +421,7 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
             // or more trees into a chunk.
             int best_t = 0, best_score = -1, best_mode = 0;
             size_t best_avail = 0;
-            int forced_tiles = 0, forced_mode = 0;   // tuning aids: FS_TUNE_TILES, FS_TUNE_MODE
-            if (const char *e = getenv("FS_TUNE_TILES"))
-                forced_tiles = atoi(e);
-            if (const char *e = getenv("FS_TUNE_MODE"))
-                forced_mode = atoi(e);
+            const int forced_tiles = tune(FS_TUNE_LDS_TILES), forced_mode = tune(FS_TUNE_LDS_MODE);
             for (int mode = kLdsModes - 1; mode >= 0 && all_trees && best_t == 0; --mode) {
                 // The half-LDS shape (two workgroups per compute unit) measured no faster on
                 // any workload and doubles the model traffic from L2: tuning aid only.
@@ -465,7 +459,7 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                     }
                 }
             }
-            if (best_t > 0 && getenv("FS_TUNE_VERBOSE"))
+            if (best_t > 0 && tune(FS_TUNE_VERBOSE) > 0)
                 fprintf(stderr, "fs_model_create: mode=%d tiles=%d avail=%zu avg_tree=%zu "
                         "max_tree=%zu compact=%d\n", best_mode, best_t, best_avail, avg_tree,
                         max_tree, (int)compact);
@@ -542,9 +536,7 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
         std::vector<uint16_t> rk_ids;
         std::vector<float> cuts;
         {
-            int want = -1;                      // tuning aid: FS_TUNE_RANK=0 never, 1 whenever possible
-            if (const char *e = getenv("FS_TUNE_RANK"))
-                want = atoi(e);
+            const int want = tune(FS_TUNE_RANK);   // -1 automatic, 0 never, 1 whenever possible
             int depth = -1;
             bool perfect = n_trees > 0 && n_features <= 511 && want != 0;
             for (int t = 0; t < n_trees && perfect; ++t) {

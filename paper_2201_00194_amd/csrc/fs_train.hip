@@ -1307,8 +1307,8 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
     }
     std::lock_guard<std::mutex> lock(g_train_mu);
     int slab_rows = kHistRowsPerSlab;
-    if (const char *e = getenv("FS_TUNE_TRAIN_SLAB_ROWS")) {     // tuning / test aid
-        const int v = atoi(e);
+    {
+        const int v = tune(FS_TUNE_TRAIN_SLAB_ROWS);             // test / tuning override
         if (v >= 64 && v <= kHistRowsPerSlab)
             slab_rows = v;
     }
@@ -1320,10 +1320,8 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
             rc = ensure_hist(trainers[i], stream);
     // deep trees of one-slab families: rows regrouped by node before level kSortLevel
     bool use_sort = n_slabs == 1 && p->max_depth >= kSortMinDepth;
-    if (const char *e = getenv("FS_TUNE_TRAIN_SORT")) {          // tuning / test aid: 0 never, 1 whenever possible
-        const int v = atoi(e);
-        use_sort = n_slabs == 1 && v != 0 && p->max_depth > kSortLevel;
-    }
+    if (tune(FS_TUNE_TRAIN_SORT) >= 0)                           // override: 0 never, 1 whenever possible
+        use_sort = n_slabs == 1 && tune(FS_TUNE_TRAIN_SORT) != 0 && p->max_depth > kSortLevel;
     if (use_sort)
         for (int i = 0; i < n_trainers && rc == FS_OK; ++i)
             rc = ensure_sort(trainers[i]);
@@ -1370,9 +1368,8 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
             ++hb;
     }
     bool packed = hb <= 31;
-    if (const char *e = getenv("FS_TUNE_TRAIN_PACKED"))          // tuning / test aid: 0 = wide form only
-        if (atoi(e) == 0)
-            packed = false;
+    if (tune(FS_TUNE_TRAIN_PACKED) == 0)                         // override: wide form only
+        packed = false;
     for (int round = 0; round < n_rounds; ++round) {
         prof_start(kKernTrainOther, stream);
         hipLaunchKernelGGL(train_begin_tree_kernel, dim3(nt), dim3(512), 0, stream, d);

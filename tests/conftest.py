@@ -17,3 +17,19 @@ def oracle():
     from oracle import oracle as O
     O.build()
     return O
+
+
+@pytest.fixture
+def tune():
+    """tune(option, value): set one of the library's test / tuning overrides (fs_tune_set) for
+    the running test; every option touched goes back to automatic afterwards."""
+    from paper_2201_00194_amd import api
+    used = []
+
+    def set_option(option, value):
+        used.append(option)
+        api.fs_tune_set(option, value)
+
+    yield set_option
+    for option in used:
+        api.fs_tune_set(option, -1)

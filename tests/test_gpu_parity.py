@@ -337,11 +337,11 @@ def test_errors_are_reported_not_raised_as_faults(api):
     torch.cuda.synchronize()
 
 
-def test_rank_coded_path_special_values_and_shallow_trees(api, oracle, monkeypatch):
+def test_rank_coded_path_special_values_and_shallow_trees(api, oracle, tune):
     """Deep perfect-tree models are walked over 16-bit ranks of the features among the model's
     own thresholds; the leaves must be the same as over the fp32 values, also for NaN, inf,
     signed zeros and denormals in features and thresholds.  Forced here for shallow trees too."""
-    monkeypatch.setenv("FS_TUNE_RANK", "1")
+    tune(api.FS_TUNE_RANK, 1)
     fams = []
     for i, (P, stm, T, dep, k) in enumerate([(700, (1, 5), 60, 10, 100), (300, (2, 2), 25, 9, 40),
                                               (500, (1, 9), 70, 6, 64), (90, (3, 3), 10, 1, 8),

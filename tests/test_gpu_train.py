@@ -87,15 +87,15 @@ def test_regularisation_and_stopping_rules(api, T):
     check(api, T, ts, rounds=2, max_depth=3, eta=0.2, lam=1.0, grad_scale=float(1 << 10))
 
 
-def test_families_spanning_several_row_slabs(api, T, monkeypatch):
+def test_families_spanning_several_row_slabs(api, T, tune):
     """Families with more rows than one histogram workgroup takes add their partial
     histograms into the global buffer and a separate kernel searches the cuts; forced here by
     shrinking the slab (a full slab is 65536 rows)."""
-    monkeypatch.setenv("FS_TUNE_TRAIN_SLAB_ROWS", "1000")
+    tune(api.FS_TUNE_TRAIN_SLAB_ROWS, 1000)
     ts = W.make_train_set(27, 900, stmts=(1, 12), n_features=21, max_cuts=100)
     assert ts.n_rows > 4000
     check(api, T, ts, rounds=4, max_depth=6, eta=0.5, lam=1.0)
-    monkeypatch.delenv("FS_TUNE_TRAIN_SLAB_ROWS")
+    tune(api.FS_TUNE_TRAIN_SLAB_ROWS, -1)
     check(api, T, ts, rounds=2, max_depth=6, eta=0.5, lam=1.0)
 
 
@@ -197,19 +197,19 @@ def test_many_tied_and_near_tied_cuts(api, T):
     check(api, T, big, rounds=3, max_depth=4, eta=0.5, lam=0.0, grad_scale=float(1 << 20))
 
 
-def test_histogram_forms_packed_wide_and_fallback(api, T, monkeypatch):
+def test_histogram_forms_packed_wide_and_fallback(api, T, tune):
     """The histogram kernel keeps (G, H) of a bin packed in one 64-bit word while the round's
     gradients leave room for it, and falls back inside the kernel to separate 64-bit sums when
-    they do not; FS_TUNE_TRAIN_PACKED=0 launches the separate sums outright.  All three must
+    they do not; the override FS_TUNE_TRAIN_PACKED = 0 launches the separate sums outright.  All three must
     give the oracle's trees.  Huge targets make the fixed-point gradients hit their clamp
     (+-2^31), so that their sum over the rows passes what the packed form can hold."""
     ts = W.make_train_set(41, 2500, stmts=(1, 40), n_features=30, max_cuts=120)
     assert 40_000 < ts.n_rows <= 65_536
     kw = dict(rounds=3, max_depth=6, eta=0.5, lam=1.0)
     check(api, T, ts, **kw)                                          # packed
-    monkeypatch.setenv("FS_TUNE_TRAIN_PACKED", "0")
+    tune(api.FS_TUNE_TRAIN_PACKED, 0)
     check(api, T, ts, **kw)                                          # wide
-    monkeypatch.delenv("FS_TUNE_TRAIN_PACKED")
+    tune(api.FS_TUNE_TRAIN_PACKED, -1)
     huge = W.TrainSet(ts.features, ts.prog_off, (ts.target * np.float32(1e7)).astype(np.float32),
                       ts.cut_off, ts.cuts)
     # the packed form has 63 - 21 bits for gradient sums here (rows x longest program < 2^21);
@@ -218,28 +218,28 @@ def test_histogram_forms_packed_wide_and_fallback(api, T, monkeypatch):
     assert 0.9 * huge.n_rows * float(1 << 31) > 2.0 ** 44
     check(api, T, huge, rounds=2, max_depth=5, eta=0.5, lam=1.0)      # fallback in the first round
     check(api, T, huge, rounds=2, max_depth=0, eta=0.5, lam=1.0)
-    monkeypatch.setenv("FS_TUNE_TRAIN_SLAB_ROWS", "20000")
+    tune(api.FS_TUNE_TRAIN_SLAB_ROWS, 20000)
     check(api, T, ts, **kw)                                          # packed, several slabs
     check(api, T, huge, rounds=2, max_depth=5, eta=0.5, lam=1.0)      # fallback, several slabs
-    monkeypatch.delenv("FS_TUNE_TRAIN_SLAB_ROWS")
+    tune(api.FS_TUNE_TRAIN_SLAB_ROWS, -1)
 
 
-def test_rows_regrouped_by_node_for_deep_trees(api, T, monkeypatch):
+def test_rows_regrouped_by_node_for_deep_trees(api, T, tune):
     """From depth 7 on the rows are regrouped once per tree by their node of level 5 and the
     deeper histograms read only their ancestors' segments; the trees must not change.  Forced on
     at depth 6, forced off at depth 9, and run with early leaves above level 5 (rows that stay
     behind) and with several families of different sizes in one batch."""
     import torch
     ts = W.make_train_set(43, 3000, stmts=(1, 9), n_features=17, max_cuts=200)
-    monkeypatch.setenv("FS_TUNE_TRAIN_SORT", "1")
+    tune(api.FS_TUNE_TRAIN_SORT, 1)
     check(api, T, ts, rounds=3, max_depth=6, eta=0.5, lam=1.0)
     check(api, T, ts, rounds=2, max_depth=9, eta=0.5, lam=0.0, min_child_weight=40.0)   # leaves above level 5
-    monkeypatch.setenv("FS_TUNE_TRAIN_PACKED", "0")
+    tune(api.FS_TUNE_TRAIN_PACKED, 0)
     check(api, T, ts, rounds=2, max_depth=8, eta=0.5, lam=1.0)                          # 8 nodes per pass
-    monkeypatch.delenv("FS_TUNE_TRAIN_PACKED")
-    monkeypatch.setenv("FS_TUNE_TRAIN_SORT", "0")
+    tune(api.FS_TUNE_TRAIN_PACKED, -1)
+    tune(api.FS_TUNE_TRAIN_SORT, 0)
     check(api, T, ts, rounds=2, max_depth=9, eta=0.5, lam=1.0)
-    monkeypatch.delenv("FS_TUNE_TRAIN_SORT")
+    tune(api.FS_TUNE_TRAIN_SORT, -1)
     sets = [W.make_train_set(50 + i, n, stmts=(1, 6), n_features=9, max_cuts=60) for i, n in enumerate((400, 2500, 60))]
     p = api.train_params(max_depth=8, eta=0.4, lam=1.0)
     trs = [api.fs_trainer.from_train_set(s, max_depth=8, max_trees=3) for s in sets]
