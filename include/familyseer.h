@@ -38,7 +38,7 @@
  *     synchronised, the old buffer freed and a larger one allocated.  A caller that has
  *     reserved enough (fs_workspace_bytes, fs_topk_workspace_bytes, fs_workspace_reserve)
  *     never gets here;
- *   - the call's descriptors (about 300 bytes per family, 48 per top-k workgroup) exceed
+ *   - the call's descriptors (about 300 bytes per family, 56 per top-k workgroup) exceed
  *     the staging capacity (64 KB unless grown before): staging is re-allocated;
  *   - descriptors are staged through a ring of 8 pinned slots per device; the ninth
  *     submission waits until the first has finished on the device.
@@ -174,6 +174,23 @@ typedef struct fs_topk_req {
  * time on different streams.
  */
 int fs_topk(int32_t n_requests, const fs_topk_req *reqs /* HOST */, void *stream);
+
+/*
+ * fs_topk for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result as fs_topk, but
+ * the call allocates nothing and never waits: descriptors and the candidate lists of sliced
+ * requests (8192 entries and more) live in a fixed 1 MiB array in device memory that the
+ * library holds on every GPU it runs on until the process ends.  Limits (FS_EUNSUPPORTED
+ * beyond them, nothing is enqueued): descriptors of at most 3584 bytes -- 56 per workgroup,
+ * one workgroup per request below 8192 entries, up to 16 per longer request, plus 48 per
+ * sliced request: about 60 workgroups; candidate lists (slices x k x 8 bytes per sliced
+ * request) of at most 1 MiB - 3584 bytes; no cut wider than 4096 on a request of 8192 or more
+ * entries.  All calls on a GPU share that GPU's array, which keeps the previous call's
+ * contents (nothing in it needs clearing: every byte a call reads it has written first): calls
+ * that overlap in time on one GPU, on whatever streams, race.  The array's device address is
+ * looked up once per device, at the first call made with that device current.
+ */
+int fs_topk_noalloc(int32_t n_requests, const fs_topk_req *reqs /* HOST */, void *stream);
 
 /* ---- library scratch ------------------------------------------------------------------- */
 

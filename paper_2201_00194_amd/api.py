@@ -65,6 +65,8 @@ _lib.fs_score_families.restype = ctypes.c_int
 _lib.fs_score_families.argtypes = [ctypes.c_int32, ctypes.POINTER(_FsFamily), ctypes.c_void_p]
 _lib.fs_topk.restype = ctypes.c_int
 _lib.fs_topk.argtypes = [ctypes.c_int32, ctypes.POINTER(_FsTopkReq), ctypes.c_void_p]
+_lib.fs_topk_noalloc.restype = ctypes.c_int
+_lib.fs_topk_noalloc.argtypes = [ctypes.c_int32, ctypes.POINTER(_FsTopkReq), ctypes.c_void_p]
 _lib.fs_pack_colblock64.restype = ctypes.c_int
 _lib.fs_pack_colblock64.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
                                     ctypes.c_void_p, ctypes.c_void_p]
@@ -222,6 +224,12 @@ def fs_topk(reqs, stream: Optional[torch.cuda.Stream] = None) -> None:
     if not isinstance(reqs, PreparedTopk):
         reqs = PreparedTopk(reqs)
     _check(_lib.fs_topk(reqs.n, reqs.arr, _stream_ptr(stream)))
+
+
+def fs_topk_noalloc(reqs, stream: Optional[torch.cuda.Stream] = None) -> None:
+    if not isinstance(reqs, PreparedTopk):
+        reqs = PreparedTopk(reqs)
+    _check(_lib.fs_topk_noalloc(reqs.n, reqs.arr, _stream_ptr(stream)))
 
 
 def fs_workspace_bytes(fams) -> int:

@@ -19,6 +19,9 @@
 // everywhere, so nothing changes in the result.  Cuts wider than 4096 do not fit that merge:
 // they are cut into slices of about 2048 entries (up to 128) whose sorted lists are merged
 // pairwise in global memory, level by level, each merge keeping the best k.
+#include <cstring>
+#include <mutex>
+
 #include "fs_internal.h"
 
 namespace fs {
@@ -398,4 +401,143 @@ int launch_topk(const TopkDesc *d_desc, int n_requests, int max_k, hipStream_t s
     return FS_OK;
 }
 
+// ---- fs_topk_noalloc: the same cut for callers that cannot allocate -----------------------------
+// Descriptors and the slices' candidate lists live in a fixed device array instead of grown
+// library scratch; the descriptors travel as a kernel argument (no staging buffer, no copy).
+constexpr size_t kNoAllocBytes = 1u << 20;        // the whole array
+constexpr size_t kNoAllocDescBytes = 3584;        // its head: descriptors (one kernel argument)
+static __device__ __align__(256) unsigned char scratch[kNoAllocBytes];
+
+struct DescBlob {
+    uint32_t words[kNoAllocDescBytes / 4];
+};
+
+__global__ void __launch_bounds__(256)
+topk_store_desc_kernel(DescBlob blob, uint32_t *dst, int n_words)
+{
+    for (int i = threadIdx.x; i < n_words; i += blockDim.x)
+        dst[i] = blob.words[i];
+}
+
+static std::mutex g_noalloc_mu;
+static unsigned char *g_noalloc_ptr[16] = {};     // device address of `scratch`, per device
+
 }  // namespace fs
+
+using namespace fs;
+
+extern "C" int fs_topk_noalloc(int32_t n_requests, const fs_topk_req *reqs, void *stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    if (n_requests < 0)
+        return fail(FS_EINVAL, "fs_topk_noalloc: n_requests %d is negative", n_requests);
+    if (n_requests == 0)
+        return FS_OK;
+    if (!reqs)
+        return fail(FS_EINVAL, "fs_topk_noalloc: reqs is NULL");
+    size_t n_blocks = 0, n_merge = 0, comp_total = 0;
+    int max_k = 0, max_comp = 0;
+    for (int i = 0; i < n_requests; ++i) {
+        const fs_topk_req &r = reqs[i];
+        if (r.n < 0 || r.k < 0)
+            return fail(FS_EINVAL, "fs_topk_noalloc: request %d: n=%d k=%d must be non-negative", i, r.n, r.k);
+        if (r.k > FS_MAX_TOPK)
+            return fail(FS_EUNSUPPORTED, "fs_topk_noalloc: request %d: k=%d exceeds FS_MAX_TOPK=%d", i,
+                        r.k, FS_MAX_TOPK);
+        if (r.n > 0 && !r.score)
+            return fail(FS_EINVAL, "fs_topk_noalloc: request %d: score is NULL", i);
+        if (r.k > 0 && !r.out_idx)
+            return fail(FS_EINVAL, "fs_topk_noalloc: request %d: out_idx is NULL", i);
+        const TopkPlan p = topk_plan(r.n, r.k);
+        if (p.mode == 2)
+            return fail(FS_EUNSUPPORTED, "fs_topk_noalloc: request %d: cuts wider than 4096 of %d or "
+                        "more entries are not served without allocation (use fs_topk)", i, kTopkSliceMin);
+        n_blocks += (size_t)p.s;
+        if (p.mode == 1) {
+            ++n_merge;
+            comp_total += (size_t)p.s * (size_t)r.k;
+            int kp = 1;
+            while (kp < r.k)
+                kp <<= 1;
+            if (p.s * kp > max_comp)
+                max_comp = p.s * kp;
+        }
+        if (r.k > max_k)
+            max_k = r.k;
+    }
+    if (max_k == 0)
+        return FS_OK;
+    const size_t merge_off = (sizeof(TopkDesc) * n_blocks + 15) & ~(size_t)15;
+    const size_t desc_bytes = merge_off + sizeof(TopkMergeDesc) * n_merge;
+    if (desc_bytes > kNoAllocDescBytes)
+        return fail(FS_EUNSUPPORTED, "fs_topk_noalloc: %zu workgroups and %zu merges need %zu bytes of "
+                    "descriptors, the limit is %zu (about 60 workgroups)", n_blocks, n_merge, desc_bytes,
+                    kNoAllocDescBytes);
+    if (comp_total * 8 > kNoAllocBytes - kNoAllocDescBytes)
+        return fail(FS_EUNSUPPORTED, "fs_topk_noalloc: the sliced requests need %zu bytes of candidate "
+                    "lists, the limit is %zu", comp_total * 8, kNoAllocBytes - kNoAllocDescBytes);
+
+    std::lock_guard<std::mutex> lock(g_noalloc_mu);
+    int dev = 0;
+    FS_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 16)
+        return fail(FS_EUNSUPPORTED, "device ordinal %d not supported", dev);
+    if (!g_noalloc_ptr[dev]) {
+        // every device holds its own copy of the array, at its own address
+        void *ptr = nullptr;
+        FS_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr)
+            return fail(FS_EDEVICE, "fs_topk_noalloc: no device address for the scratch array");
+        g_noalloc_ptr[dev] = (unsigned char *)ptr;
+    }
+    unsigned char *base = g_noalloc_ptr[dev];
+
+    DescBlob blob;
+    memset(&blob, 0, sizeof(blob));
+    TopkDesc *h = (TopkDesc *)blob.words;
+    TopkMergeDesc *hm = (TopkMergeDesc *)((unsigned char *)blob.words + merge_off);
+    unsigned long long *comp = (unsigned long long *)(base + kNoAllocDescBytes);
+    size_t b = 0, m = 0;
+    for (int i = 0; i < n_requests; ++i) {
+        const fs_topk_req &r = reqs[i];
+        const TopkPlan p = topk_plan(r.n, r.k);
+        for (int j = 0; j < p.s; ++j, ++b) {
+            h[b].score = r.score;
+            h[b].out_idx = r.out_idx;
+            h[b].out_score = r.out_score;
+            h[b].n = r.n;
+            h[b].k = r.k;
+            const long long lo = (long long)j * p.per, hi = lo + p.per;
+            h[b].sub_begin = (int32_t)(lo < r.n ? lo : r.n);
+            h[b].sub_end = (int32_t)(hi < r.n ? hi : r.n);
+            h[b].comp_pad = p.mode == 1 ? 1 : 0;
+            h[b].pad = 0;
+            h[b].comp_out = p.mode == 1 ? comp + (size_t)j * (size_t)r.k : nullptr;
+        }
+        if (p.mode == 1) {
+            hm[m].comp_in = comp;
+            hm[m].score = r.score;
+            hm[m].out_idx = r.out_idx;
+            hm[m].out_score = r.out_score;
+            hm[m].n_comp = p.s * r.k;
+            hm[m].n = r.n;
+            hm[m].k = r.k;
+            hm[m].pad = 0;
+            comp += (size_t)p.s * (size_t)r.k;
+            ++m;
+        }
+    }
+    // Nothing in the array has to start at zero: every workgroup writes its whole list (padding
+    // included) before the merge reads it, and the descriptors are rewritten by every call.
+    hipLaunchKernelGGL(topk_store_desc_kernel, dim3(1), dim3(256), 0, stream, blob, (uint32_t *)base,
+                       (int)((desc_bytes + 3) / 4));
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail_hip(e, "topk_store_desc_kernel launch");
+    prof_start(kKernTopk, stream);
+    int rc = launch_topk((const TopkDesc *)base, (int)n_blocks, max_k, stream);
+    if (rc == FS_OK && n_merge)
+        rc = launch_topk_merge((const TopkMergeDesc *)(base + merge_off), (int)n_merge, max_comp, stream);
+    prof_stop(stream);
+    return rc;
+}
