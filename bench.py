@@ -86,13 +86,13 @@ def recorded_traffic(config: int):
     return ent.get("hbm_bytes_per_launch")
 
 
-def mean_path_length(case, sample_rows: int = 512):
-    """(mean splits per (row, tree) on a row sample via the oracle's leaf ids, walked levels
-    per (row, tree) in the kernel's lock-step walk)."""
+def mean_path_length(case, devs, api, torch, sample_rows: int = 512):
+    """(mean splits per (row, tree) on a row sample, from the leaf ids the library itself reports
+    for the first rows of every family; walked levels per (row, tree) in a lock-step walk to the
+    deepest leaf; (row, tree) pairs of the workload)."""
     import numpy as np
-    from oracle import oracle as O
     tot, cnt, lock = 0.0, 0, 0.0
-    for f in case.families:
+    for f, d in zip(case.families, devs):
         m = f.model
         if m.n_trees == 0 or f.n_rows == 0:
             continue
@@ -110,8 +110,12 @@ def mean_path_length(case, sample_rows: int = 512):
             depth[gr] = depth[internal] + 1
             if np.array_equal(before, depth):
                 break
-        rows = np.linspace(0, f.n_rows - 1, min(sample_rows, f.n_rows)).astype(np.int64)
-        li = O.leaf_indices(m, f.features[rows])
+        nr = min(sample_rows, f.n_rows)
+        leaf = torch.zeros(nr * m.n_trees, dtype=torch.int16, device="cuda")
+        off = torch.tensor([0, nr], dtype=torch.int32, device="cuda")
+        ps = torch.zeros(1, dtype=torch.float32, device="cuda")
+        api.fs_score_families([api.Family(d.model, d.features, api.FS_COLBLOCK64, nr, off, ps, None, leaf)])
+        li = leaf.cpu().numpy().view(np.uint16).reshape(nr, m.n_trees).astype(np.int64)
         dl = depth[m.tree_off[:-1][None, :] + li]
         tot += float(dl.mean()) * f.n_rows * m.n_trees
         cnt += f.n_rows * m.n_trees
@@ -380,21 +384,21 @@ def main():
         "workload_gen_s": round(gen_s, 2),
     }
 
+    # ---- what actually binds the kernel: LDS instruction issue of the visit loop ---------------
+    mean_path, lock_path, pairs = mean_path_length(case, devs, api, torch)
+    visits_alg = mean_path * pairs
+    visits_walked = lock_path * pairs
+    out["visit_roofline"] = {
+        "bound": "lds-issue", "unit": "node visits/s",
+        "achieved_algorithmic": round(visits_alg / (trav_avg_ms * 1e-3), 1),
+        "achieved_walked": round(visits_walked / (trav_avg_ms * 1e-3), 1),
+        "peak": LDS_VISIT_PEAK,
+        "frac_walked": round(visits_walked / (trav_avg_ms * 1e-3) / LDS_VISIT_PEAK, 4),
+        "mean_path": round(mean_path, 3), "walked_levels": round(lock_path, 3)}
+
     if not args.no_cpu_baseline:
         from oracle import oracle as O
         O.build()
-        # ---- what actually binds the kernel: LDS instruction issue of the visit loop -----------
-        mean_path, lock_path, pairs = mean_path_length(case)
-        visits_alg = mean_path * pairs
-        visits_walked = lock_path * pairs
-        out["visit_roofline"] = {
-            "bound": "lds-issue", "unit": "node visits/s",
-            "achieved_algorithmic": round(visits_alg / (trav_avg_ms * 1e-3), 1),
-            "achieved_walked": round(visits_walked / (trav_avg_ms * 1e-3), 1),
-            "peak": LDS_VISIT_PEAK,
-            "frac_walked": round(visits_walked / (trav_avg_ms * 1e-3) / LDS_VISIT_PEAK, 4),
-            "mean_path": round(mean_path, 3), "walked_levels": round(lock_path, 3)}
-
         # ---- CPU baseline: the oracle as it stands, on a bounded sample --------------------------
         threads = min(16, os.cpu_count() or 1)
         budget = 2.0e10                     # node visits: roughly 30 core-seconds of the oracle
