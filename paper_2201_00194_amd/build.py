@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfamilyseer.so")
+CEILINGS = os.path.join(HERE, "fs_ceilings.bin")   # stand-alone microbenchmarks (csrc/fs_ceilings.hip)
 
 SOURCES = ["fs_api.hip", "fs_model.hip", "fs_traverse_lds.hip", "fs_rank.hip", "fs_traverse_global.hip", "fs_segsum.hip", "fs_topk.hip", "fs_pack.hip", "fs_train.hip", "fs_gather.hip"]
 
@@ -34,6 +35,13 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
+    cmd = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+           os.path.join(CSRC, "fs_ceilings.hip"), "-o", CEILINGS]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed (fs_ceilings):\n" +
+                           "\n".join(l for l in res.stderr.splitlines() if noise not in l))
     return LIB
 
 

@@ -114,7 +114,7 @@ static int ensure_scratch(DeviceCtx *ctx, int which, size_t floats, bool exact =
 
 // ---- test and tuning overrides -----------------------------------------------------------------
 static std::mutex g_tune_mu;
-static int g_tune[FS_TUNE_OPTIONS] = {-1, -1, -1, -1, -1, -1, -1, -1, -1};
+static int g_tune[FS_TUNE_OPTIONS] = {-1, -1, -1, -1, -1, -1, -1, -1};
 
 int tune(int option)
 {
