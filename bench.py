@@ -25,9 +25,19 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# LDS issue ceiling of the visit loop: 256 CUs x 2.4 GHz, one visit = an 8-byte node and a
-# 4-byte feature per lane = 768 B per wavefront at 128 B/clk/CU -> 6 clk per 64 visits.
-LDS_VISIT_PEAK = 256 * 2.4e9 * 64 / 6.0
+
+
+def measured_ceilings() -> dict:
+    """The JSON line of profiles/ceilings_mi355x.txt (output of fs_ceilings.bin on an MI355X):
+    measured HBM read stream, LDS read rates and the synthetic visit loop.  {} if absent."""
+    path = os.path.join(ROOT, "profiles", "ceilings_mi355x.txt")
+    try:
+        for line in open(path):
+            if line.startswith("JSON "):
+                return json.loads(line[5:])
+    except (OSError, ValueError):
+        pass
+    return {}
 
 
 def parse():
@@ -351,10 +361,14 @@ def main():
     alg_bytes = sum(f.n_rows * (f.model.n_features * 4 + 4) for f in case.families) + model_bytes
     trav_avg_ms = trav_ms / max(1, trav_n)
     achieved = alg_bytes / (trav_avg_ms * 1e-3) / 1e9 if trav_avg_ms > 0 else 0.0
+    ceil = measured_ceilings()
+    stream = ceil.get("hbm_read_stream_gbs")
     roofline = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None if args.foresee else recorded_traffic(args.config),
                 "kernel": kname, "kernel_avg_ms": round(trav_avg_ms, 5),
-                "algorithmic_bytes_per_launch": int(alg_bytes)}
+                "algorithmic_bytes_per_launch": int(alg_bytes),
+                "measured_read_stream": stream,
+                "frac_of_measured_stream": round(achieved / stream, 5) if stream else None}
 
     out = {
         "metric": "statement-rows scored/sec + achieved HBM GB/s (% of peak); per-family top-k us",
@@ -388,12 +402,17 @@ def main():
     mean_path, lock_path, pairs = mean_path_length(case, devs, api, torch)
     visits_alg = mean_path * pairs
     visits_walked = lock_path * pairs
+    # peak: one node read + one feature read per visit at the measured conflict-free LDS rate;
+    # synthetic_loop: what a lock-step walk with nothing else around it reaches on this chip
+    vpeak, vloop = ceil.get("visit_peak_conflict_free"), ceil.get("visit_loop_measured")
+    walked_rate = visits_walked / (trav_avg_ms * 1e-3)
     out["visit_roofline"] = {
         "bound": "lds-issue", "unit": "node visits/s",
         "achieved_algorithmic": round(visits_alg / (trav_avg_ms * 1e-3), 1),
-        "achieved_walked": round(visits_walked / (trav_avg_ms * 1e-3), 1),
-        "peak": LDS_VISIT_PEAK,
-        "frac_walked": round(visits_walked / (trav_avg_ms * 1e-3) / LDS_VISIT_PEAK, 4),
+        "achieved_walked": round(walked_rate, 1),
+        "peak": vpeak, "frac_walked": round(walked_rate / vpeak, 4) if vpeak else None,
+        "synthetic_loop": vloop,
+        "frac_walked_of_synthetic_loop": round(walked_rate / vloop, 4) if vloop else None,
         "mean_path": round(mean_path, 3), "walked_levels": round(lock_path, 3)}
 
     if not args.no_cpu_baseline:

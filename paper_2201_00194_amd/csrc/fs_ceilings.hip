@@ -26,14 +26,21 @@
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// UNROLL loads in flight per thread (1: the plain grid-stride loop).
+template <int UNROLL>
 __global__ void __launch_bounds__(512) stream_read_kernel(const u32x4 *__restrict__ p, size_t n16, uint32_t *out)
 {
     size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     uint32_t acc = 0;
-    for (; i + 3 * stride < n16; i += 4 * stride) {          // four loads in flight per thread
-        const u32x4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
-        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    for (; i + (UNROLL - 1) * stride < n16; i += UNROLL * stride) {
+        u32x4 v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            v[u] = p[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
     for (; i < n16; i += stride) {
         const u32x4 a = p[i];
@@ -275,22 +282,25 @@ int main()
         hipEvent_t e0, e1;
         CK(hipEventCreate(&e0));
         CK(hipEventCreate(&e1));
-        for (int blocks : {n_cu * 8, n_cu * 16, n_cu * 32}) {
-            stream_read_kernel<<<blocks, 512>>>(d, bytes / 16, d_out);
-            CK(hipDeviceSynchronize());
-            CK(hipEventRecord(e0));
-            for (int r = 0; r < 5; ++r)
-                stream_read_kernel<<<blocks, 512>>>(d, bytes / 16, d_out);
-            CK(hipEventRecord(e1));
-            CK(hipEventSynchronize(e1));
-            float ms;
-            CK(hipEventElapsedTime(&ms, e0, e1));
-            ms /= 5;
-            const double gbs = bytes / (ms * 1e-3) / 1e9;
-            printf("  %5zu MiB, %5d workgroups of 512: %.3f ms = %.0f GB/s\n", mb, blocks, ms, gbs);
-            if (gbs > best_gbs)
-                best_gbs = gbs;
-        }
+        for (int unroll : {1, 4})
+            for (int blocks : {n_cu * 8, n_cu * 16, n_cu * 32}) {
+                auto kern = unroll == 1 ? stream_read_kernel<1> : stream_read_kernel<4>;
+                kern<<<blocks, 512>>>(d, bytes / 16, d_out);
+                CK(hipDeviceSynchronize());
+                CK(hipEventRecord(e0));
+                for (int r = 0; r < 5; ++r)
+                    kern<<<blocks, 512>>>(d, bytes / 16, d_out);
+                CK(hipEventRecord(e1));
+                CK(hipEventSynchronize(e1));
+                float ms;
+                CK(hipEventElapsedTime(&ms, e0, e1));
+                ms /= 5;
+                const double gbs = bytes / (ms * 1e-3) / 1e9;
+                printf("  %5zu MiB, %5d workgroups of 512, %d load(s) in flight per thread: %.3f ms = %.0f GB/s\n",
+                       mb, blocks, unroll, ms, gbs);
+                if (gbs > best_gbs)
+                    best_gbs = gbs;
+            }
         CK(hipFree(d));
     }
 

@@ -253,3 +253,13 @@ def test_rows_regrouped_by_node_for_deep_trees(api, T, tune):
         rows, progs = tr.predictions()
         torch.cuda.synchronize()
         assert np.array_equal(rows.cpu().numpy().view(np.uint32), exp.row_pred.view(np.uint32))
+
+
+def test_family_of_the_benchmark_workloads_own_size(api, T):
+    """One family of the workload `bench.py --train` times, at its own size: the largest of the
+    eight (164 features, 255 cuts, tens of thousands of rows in one histogram slab), two rounds
+    at the benchmark's depth and parameters."""
+    sets = W.make_train_case(seed=0)
+    ts = max(sets, key=lambda s: s.n_rows)
+    assert ts.features.shape[1] == 164 and 30_000 < ts.n_rows <= 65_536
+    check(api, T, ts, rounds=2, max_depth=6, eta=0.2, lam=1.0)
