@@ -33,9 +33,9 @@ int tune(int option);
 typedef int4 GNode;
 
 // ---- LDS-staged model format -------------------------------------------------------------------
-// The ensemble is cut into chunks.  A chunk is a byte image that is copied verbatim to LDS
-// offset 0:
-//     [n_trees x uint32: byte offset of each tree's root] [nodes ...]   (size multiple of 16)
+// The ensemble is cut into chunks of consecutive trees.  A chunk is a byte image that is copied
+// verbatim to LDS offset 0:
+//     [run records of the wavefront slots] [further run records] [nodes ...]   (multiple of 16)
 // A node is 8 bytes {w0, w1}:
 //     internal: w0 = threshold bits, w1 = (feature * 256) << 16 | byte offset of the LEFT child;
 //               the right child sits right after the left one
@@ -43,11 +43,23 @@ typedef int4 GNode;
 //               it reads the all-NaN column, fails '<' and so steps back onto itself
 // In "compact" chunks (every tree of the model perfect and of one depth >= 1) leaves are 4-byte
 // values only, laid out after the tree's internal nodes; the last split level then steps by 4.
+//
+// Walk order.  The wavefronts that share a tile ("slots") split the chunk's trees.  Trees are
+// sorted by depth and cut into runs of at most 8 trees of similar depth; a run is walked side by
+// side, to the depth of its first (deepest) tree, and the runs are dealt to the slots so that the
+// slots have about the same work.  A run record is kRunWords uint32: word 0 = number of trees
+// (bits 0-3) | index of the slot's next run record + 1, or 0 (bits 4-15) | depth (bits 16-31);
+// words 1..8 = the run's trees: LDS offset of the root (bits 0-15) | index of the tree in its
+// chunk, i.e. the place the ordered sum gives it (bits 16-23); unused tree words repeat the first.
+// Record s (s < kLdsMaxWaves) is the first run of slot s (no trees: the slot is idle).
+constexpr int kRunWords = 9;
+constexpr int kRunBytes = 4 * kRunWords;
+
 struct ChunkHdr {
     uint32_t byte_off;    // into the packed image
     uint32_t bytes;       // multiple of 16
     uint32_t n_trees;
-    uint32_t depth;       // split levels to walk (max over the chunk's trees)
+    uint32_t depth;       // split levels of the deepest tree of the chunk
     uint32_t first_tree;  // model-wide index of the chunk's first tree
     uint32_t slot_off;    // into the id map: entry [slot_off + (lds byte offset >> 2)]
     uint32_t pad0;
@@ -55,7 +67,7 @@ struct ChunkHdr {
 };
 
 // LDS map of the traversal kernel (bytes):
-//   [0, chunk bytes)                       model chunk
+//   [0, chunk bytes)                       model chunk (run records, nodes)
 //   [tile0 - n_trees*tiles*256, tile0)     leaf values [tree in chunk][tile][lane] (fp32)
 //   [tile0, 160 KB)                        `tiles` feature tiles of (n_features+1)*256 bytes,
 //                                          tile0 = 160 KB - tiles * tile bytes

@@ -174,6 +174,132 @@ static int chunk_tree_target(int n_trees, int fit, int share)
     return best;
 }
 
+// ---- chunk plan of the LDS-staged format --------------------------------------------------------
+// The wavefronts that share a tile (`share` of them) split a chunk's trees; every wavefront
+// walks its trees in runs of at most 8, side by side, a run to the depth of its deepest tree.
+// Trees are therefore sorted by depth and cut into runs of similar depth (the cheapest cut of
+// the sorted list into runs no longer than an even split would make them), and the runs are
+// dealt out most expensive first, each to the wavefront with the least work so far.  Cost in the
+// planner's units (weights fitted to measurements on depth-8 trees: one chunk with one run of few
+// trees = 1): a chunk costs 0.73 (copy, barriers, ordered sum) + the work of its busiest
+// wavefront, a run (0.034 + 0.022 x trees of the run) x (levels of the run + 1).
+struct RunPlan {
+    int first, count, depth;         // walk-order entries [first, first + count)
+};
+struct SlotPlan {
+    std::vector<int> order;          // trees of the chunk (indices relative to it) in walk order
+    std::vector<RunPlan> runs;       // in walk order: the runs of slot 0, then of slot 1, ...
+    int slot_start[17];              // slot s walks runs [slot_start[s], slot_start[s + 1])
+    double cost;
+};
+
+static double run_cost(int trees, int levels) { return (0.034 + 0.022 * trees) * (levels + 1); }
+
+// `by_depth`: the chunk's trees (relative indices) sorted by depth, deepest first.
+static void deal_trees(const std::vector<int> &by_depth, const int *depth, int share, SlotPlan *out)
+{
+    const int n = (int)by_depth.size();
+    const int rounds = (n + 8 * share - 1) / (8 * share);
+    int cap = (n + share * rounds - 1) / (share * rounds);
+    if (cap > 8) cap = 8;
+    if (cap < 1) cap = 1;
+    struct Piece { int first, count; double cost; };
+    std::vector<Piece> pieces;
+    std::vector<int> list;           // the trees in the order the pieces index
+    // Plain plan: the trees in their own order, share x rounds runs whose sizes differ by at most
+    // one, every run to the depth of its deepest tree.
+    long plain_levels = 0;
+    {
+        const int n_runs = share * rounds, base = n / n_runs, rem = n - base * n_runs;
+        for (int j = 0, at = 0; j < n_runs; ++j) {
+            const int cnt = base + (j < rem ? 1 : 0);
+            int d = 0;
+            for (int k = 0; k < cnt; ++k)
+                d = std::max(d, depth[at + k]);
+            plain_levels += (long)cnt * d;
+            at += cnt;
+        }
+    }
+    // Sorted plan: cheapest cut of the depth-sorted list into runs of at most `cap`
+    std::vector<double> best((size_t)n + 1, 1e300);
+    std::vector<int> from((size_t)n + 1, 0);
+    best[0] = 0.0;
+    for (int i = 0; i < n; ++i)
+        for (int c = 1; c <= cap && i + c <= n; ++c) {
+            const double v = best[(size_t)i] + run_cost(c, depth[by_depth[(size_t)i]]);
+            if (v < best[(size_t)(i + c)] - 1e-12) {
+                best[(size_t)(i + c)] = v;
+                from[(size_t)(i + c)] = i;
+            }
+        }
+    long sorted_levels = 0;
+    for (int j = n; j > 0; j = from[(size_t)j]) {
+        pieces.push_back({from[(size_t)j], j - from[(size_t)j],
+                          run_cost(j - from[(size_t)j], depth[by_depth[(size_t)from[(size_t)j]]])});
+        sorted_levels += (long)(j - from[(size_t)j]) * depth[by_depth[(size_t)from[(size_t)j]]];
+    }
+    // Sorting pays when it takes a tenth of the walked levels away (measured: with fewer shallow
+    // trees the uneven wavefronts it leaves cost what the skipped levels save).
+    const bool sorted = 10 * sorted_levels <= 9 * plain_levels;
+    if (sorted) {
+        list = by_depth;
+        std::reverse(pieces.begin(), pieces.end());  // deepest (most expensive per tree) first
+        std::stable_sort(pieces.begin(), pieces.end(), [](const Piece &x, const Piece &y) { return x.cost > y.cost; });
+    } else {
+        pieces.clear();
+        list.resize((size_t)n);
+        for (int j = 0; j < n; ++j)
+            list[(size_t)j] = j;
+        const int n_runs = share * rounds, base = n / n_runs, rem = n - base * n_runs;
+        for (int j = 0, at = 0; j < n_runs; ++j) {
+            const int cnt = base + (j < rem ? 1 : 0);
+            if (cnt == 0)
+                continue;
+            // the kernel walks a run to the depth of its FIRST tree: put the deepest first
+            int deepest = at;
+            for (int k = 1; k < cnt; ++k)
+                if (depth[at + k] > depth[deepest])
+                    deepest = at + k;
+            std::swap(list[(size_t)at], list[(size_t)deepest]);
+            pieces.push_back({at, cnt, run_cost(cnt, depth[list[(size_t)at]])});
+            at += cnt;
+        }
+    }
+    std::vector<std::vector<Piece>> bins((size_t)share);
+    std::vector<double> load((size_t)share, 0.0);
+    if (sorted) {
+        for (const Piece &pc : pieces) {
+            int to = 0;
+            for (int b = 1; b < share; ++b)
+                if (load[(size_t)b] < load[(size_t)to] - 1e-12)
+                    to = b;
+            bins[(size_t)to].push_back(pc);
+            load[(size_t)to] += pc.cost;
+        }
+    } else {
+        for (size_t j = 0; j < pieces.size(); ++j) {      // run j to slot j mod share
+            bins[j % (size_t)share].push_back(pieces[j]);
+            load[j % (size_t)share] += pieces[j].cost;
+        }
+    }
+    out->order.clear();
+    out->runs.clear();
+    out->cost = 0.0;
+    for (int b = 0; b < share; ++b) {
+        out->slot_start[b] = (int)out->runs.size();
+        for (const Piece &pc : bins[(size_t)b]) {
+            out->runs.push_back({(int)out->order.size(), pc.count, depth[list[(size_t)pc.first]]});
+            for (int j = 0; j < pc.count; ++j)
+                out->order.push_back(list[(size_t)(pc.first + j)]);
+        }
+        if (load[(size_t)b] > out->cost)
+            out->cost = load[(size_t)b];
+    }
+    for (int b = share; b <= 16; ++b)
+        out->slot_start[b] = (int)out->runs.size();
+    out->cost += 0.73;
+}
+
 size_t chunk_image_limit(int mode)
 {
     const size_t by_regs = (size_t)kLdsModeWaves[mode] * 64 * kPrefetchRegs * 16;
@@ -436,13 +562,15 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                         continue;
                     const long avail = (long)kLdsModeBytes[mode] - (long)nt * tile_bytes - 64;
                     const size_t per_tree_val = (size_t)nt * 256;
-                    if (avail < (long)(max_tree + 16 + per_tree_val))
+                    const size_t per_tree_tab = 4;   // a tree word of a run record
+                    const size_t head = (size_t)(kLdsMaxWaves + 12) * kRunBytes + 16;   // records + padding
+                    if (avail < (long)(max_tree + head + per_tree_val))
                         continue;
                     const size_t max_img = chunk_image_limit(mode);
-                    if (max_img < max_tree + 16)
+                    if (max_img < max_tree + head)
                         continue;
-                    size_t by_chunk = (max_img - 16) / (avg_tree + 4);
-                    size_t by_avail = ((size_t)avail - 16) / (avg_tree + 4 + per_tree_val);
+                    size_t by_chunk = (max_img - head) / (avg_tree + per_tree_tab);
+                    size_t by_avail = ((size_t)avail - head) / (avg_tree + per_tree_tab + per_tree_val);
                     size_t per = by_chunk < by_avail ? by_chunk : by_avail;
                     if (per < 1) per = 1;
                     if (per > (size_t)kMaxChunkTrees) per = kMaxChunkTrees;
@@ -470,30 +598,57 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                 m->lds_tiles = best_t;
                 m->lds_mode = best_mode;
                 // Trees per chunk: estimated from the average tree, then balanced over the
-                // wavefronts that share a tile (chunk_tree_target).
-                size_t est_per = best_avail / (avg_tree + 4 + per_tree_val);
-                const size_t est_img = (chunk_image_limit(best_mode) - 16) / (avg_tree + 4);
+                // wavefronts that share a tile (chunk_tree_target); a chunk ends early if its
+                // trees are larger than average and the next one does not fit.
+                const int share = kLdsModeWaves[best_mode] / best_t;
+                const size_t img_limit = chunk_image_limit(best_mode);
+                std::vector<int> tdepth((size_t)n_trees);
+                for (int t = 0; t < n_trees; ++t)
+                    tdepth[(size_t)t] = trees[(size_t)t].depth;
+                // (every tree may need a run record of its own on top of the slots' first records)
+                const size_t head0 = (size_t)kLdsMaxWaves * kRunBytes + 16;
+                size_t est_per = (best_avail - head0) / (avg_tree + kRunBytes + per_tree_val);
+                const size_t est_img = (img_limit - head0) / (avg_tree + kRunBytes);
                 if (est_per > est_img) est_per = est_img;
                 if (est_per > (size_t)kMaxChunkTrees) est_per = kMaxChunkTrees;
                 if (est_per < 1) est_per = 1;
-                const int even_cap = chunk_tree_target(n_trees, (int)est_per, kLdsModeWaves[best_mode] / best_t);
-                int t = 0;
-                while (t < n_trees) {
-                    // how many trees fit: chunk image (table included) + their value rows
+                const int even_cap = chunk_tree_target(n_trees, (int)est_per, share);
+                std::vector<int> bounds(1, 0);
+                for (int t = 0; t < n_trees;) {
                     int cnt = 0;
                     size_t body = 0;
                     while (t + cnt < n_trees && cnt < kMaxChunkTrees && cnt < even_cap) {
-                        const size_t b = trees[(size_t)(t + cnt)].words.size() * 4;
-                        const size_t table = ((size_t)(cnt + 1) * 4 + 7) & ~(size_t)7;
-                        const size_t img = (table + body + b + 15) & ~(size_t)15;
-                        if (img > chunk_image_limit(best_mode) ||
-                            img + (size_t)(cnt + 1) * per_tree_val > best_avail)
+                        const size_t bt = trees[(size_t)(t + cnt)].words.size() * 4;
+                        // run records in front of the nodes: at most one per slot and one per tree
+                        const size_t img = ((size_t)(kLdsMaxWaves + cnt + 1) * kRunBytes + body + bt + 15) & ~(size_t)15;
+                        if (img > img_limit || img + (size_t)(cnt + 1) * per_tree_val > best_avail)
                             break;
-                        body += b;
+                        body += bt;
                         ++cnt;
                     }
-                    // cnt >= 1 by the choice of best_t
-                    const size_t table = ((size_t)cnt * 4 + 7) & ~(size_t)7;
+                    t += cnt;                                 // cnt >= 1 by the choice of best_t
+                    bounds.push_back(t);
+                }
+                for (size_t ci = 0; ci + 1 < bounds.size(); ++ci) {
+                    const int t = bounds[ci], cnt = bounds[ci + 1] - bounds[ci];
+                    size_t body = 0;
+                    for (int j = 0; j < cnt; ++j)
+                        body += trees[(size_t)(t + j)].words.size() * 4;
+                    std::vector<int> by_depth((size_t)cnt);
+                    for (int j = 0; j < cnt; ++j)
+                        by_depth[(size_t)j] = j;
+                    std::stable_sort(by_depth.begin(), by_depth.end(), [&](int x, int y) {
+                        return tdepth[(size_t)(t + x)] > tdepth[(size_t)(t + y)];
+                    });
+                    SlotPlan sp;
+                    deal_trees(by_depth, tdepth.data() + t, share, &sp);
+                    // records: one per slot first (its first run, or an empty one), then the rest
+                    std::vector<int> rec_of(sp.runs.size(), -1);     // record index of every run
+                    int n_rec = kLdsMaxWaves;
+                    for (int b = 0; b < share; ++b)
+                        for (int r = sp.slot_start[b]; r < sp.slot_start[b + 1]; ++r)
+                            rec_of[(size_t)r] = r == sp.slot_start[b] ? b : n_rec++;
+                    const size_t table = ((size_t)n_rec * kRunBytes + 7) & ~(size_t)7;
                     const size_t bytes = (table + body + 15) & ~(size_t)15;
                     ChunkHdr h;
                     memset(&h, 0, sizeof(h));
@@ -508,10 +663,11 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                     uint16_t *ids = slot_ids.data() + h.slot_off;
                     size_t pos = table;
                     uint32_t dmax = 0;
+                    std::vector<uint32_t> root_at((size_t)cnt);
                     for (int j = 0; j < cnt; ++j) {
                         PackedTree &pt = trees[(size_t)(t + j)];
                         const uint32_t base = (uint32_t)pos;
-                        memcpy(img + 4 * j, &base, 4);
+                        root_at[(size_t)j] = base;
                         for (uint32_t wi : pt.fix) {
                             const uint32_t w = pt.words[wi];
                             pt.words[wi] = (w & 0xFFFF0000u) | (((w & 0xFFFFu) + base) & 0xFFFFu);
@@ -522,8 +678,25 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                         if ((uint32_t)pt.depth > dmax) dmax = (uint32_t)pt.depth;
                     }
                     h.depth = dmax;
+                    for (int b = 0; b < share; ++b)
+                        for (int r = sp.slot_start[b]; r < sp.slot_start[b + 1]; ++r) {
+                            const RunPlan &rp = sp.runs[(size_t)r];
+                            const int next = r + 1 < sp.slot_start[b + 1] ? rec_of[(size_t)(r + 1)] + 1 : 0;
+                            uint32_t rec[kRunWords];
+                            rec[0] = (uint32_t)rp.count | ((uint32_t)next << 4) | ((uint32_t)rp.depth << 16);
+                            for (int k = 0; k < 8; ++k) {
+                                const int j = sp.order[(size_t)(rp.first + (k < rp.count ? k : 0))];
+                                rec[1 + k] = root_at[(size_t)j] | ((uint32_t)j << 16);
+                            }
+                            memcpy(img + (size_t)rec_of[(size_t)r] * kRunBytes, rec, sizeof(rec));
+                        }
                     chunks.push_back(h);
-                    t += cnt;
+                }
+                if (tune(FS_TUNE_VERBOSE) > 0) {
+                    fprintf(stderr, "fs_model_create: %zu chunks, trees per chunk:", chunks.size());
+                    for (const ChunkHdr &c : chunks)
+                        fprintf(stderr, " %u", c.n_trees);
+                    fprintf(stderr, "\n");
                 }
                 m->n_chunks = (int32_t)chunks.size();
                 m->image_bytes = image.size();

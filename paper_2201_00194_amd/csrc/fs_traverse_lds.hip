@@ -15,7 +15,8 @@
 // by parking its leaf value in LDS; one wavefront per tile then adds the chunk's values to
 // the row's running sum in tree order, so the row score has the bits of a plain
 // sequential fp32 sum.  The next chunk is fetched into registers while the current one is
-// being walked.
+// being walked.  A chunk's trees are cut into runs of similar depth that are dealt to the
+// wavefronts (run records at the head of the chunk image).
 //
 // LDS map:  [0, chunk bytes)                    current model chunk (node offsets are
 //                                               absolute LDS addresses)
@@ -30,16 +31,23 @@ namespace fs {
 
 constexpr int kTileBatch = 8;    // 16-byte loads in flight per thread while tiles are fetched
 
-// Walk K trees of the current chunk for this lane's row.  root[k] are LDS byte offsets; on
-// return a[k] is the LDS offset of the leaf reached and v[k] its value.
+// One run: K trees of the current chunk, walked side by side for this lane's row to `depth`
+// split levels (the depth of the run's deepest tree; a walk that reaches its leaf earlier stays
+// there).  `tab` holds the tree words of the run record (root offset | place in the chunk).
+// Every walk parks its leaf value in the value row of its tree; DUMP also reports the leaf ids.
 // COMPACT: perfect trees with 4-byte leaves, so the last split level steps by 4.
-template <int K, bool COMPACT>
-__device__ __forceinline__ void walk_group(const uint32_t (&root)[K], int depth,
-                                           uint32_t lane_base, uint32_t (&a)[K], float (&v)[K])
+template <int K, bool COMPACT, bool DUMP>
+__device__ __forceinline__ void walk_k(const uint32_t (&tab)[8], int depth, uint32_t lane_base,
+                                       uint32_t val_addr, uint32_t val_stride,
+                                       const uint16_t *slot_ids_, uint16_t *leaf_out_)
 {
+    auto slot_ids = FS_GLOBAL(const uint16_t, slot_ids_);
+    auto leaf_out = FS_GLOBAL(uint16_t, leaf_out_);
+    uint32_t a[K];
+    float v[K];
 #pragma unroll
     for (int k = 0; k < K; ++k)
-        a[k] = root[k];
+        a[k] = tab[k] & 0xFFFFu;
     const int full_levels = COMPACT ? depth - 1 : depth;
     for (int l = 0; l < full_levels; ++l) {
         u32x2 nd[K];
@@ -70,50 +78,51 @@ __device__ __forceinline__ void walk_group(const uint32_t (&root)[K], int depth,
 #pragma unroll
     for (int k = 0; k < K; ++k)
         v[k] = lds_f(a[k]);
-}
-
-// Trees [g, g+K) of the chunk: walk, park the leaf values, optionally report the leaf ids.
-template <int K, bool COMPACT, bool DUMP>
-__device__ __forceinline__ void walk_k(int g, int depth, uint32_t lane_base, uint32_t val_addr,
-                                       uint32_t val_stride, const uint16_t *slot_ids_,
-                                       uint16_t *leaf_out_)
-{
-    auto slot_ids = FS_GLOBAL(const uint16_t, slot_ids_);
-    auto leaf_out = FS_GLOBAL(uint16_t, leaf_out_);
-    uint32_t root[K], a[K];
-    float v[K];
 #pragma unroll
     for (int k = 0; k < K; ++k)
-        root[k] = lds_u(4u * (uint32_t)(g + k));        // same address in every lane: broadcast
-    walk_group<K, COMPACT>(root, depth, lane_base, a, v);
-#pragma unroll
-    for (int k = 0; k < K; ++k)
-        lds_store_f(val_addr + (uint32_t)(g + k) * val_stride, v[k]);
+        lds_store_f(val_addr + (tab[k] >> 16) * val_stride, v[k]);
     if (DUMP) {
         if (leaf_out_) {
 #pragma unroll
             for (int k = 0; k < K; ++k)
-                leaf_out[g + k] = slot_ids[a[k] >> 2];
+                leaf_out[tab[k] >> 16] = slot_ids[a[k] >> 2];
         }
     }
 }
 
 template <bool COMPACT, bool DUMP>
-__device__ __forceinline__ void walk_n(int count, int g, int depth, uint32_t lane_base,
+__device__ __forceinline__ void walk_n(int count, const uint32_t (&tab)[8], int depth, uint32_t lane_base,
                                        uint32_t val_addr, uint32_t val_stride,
                                        const uint16_t *slot_ids, uint16_t *leaf_out)
 {
     switch (count) {
-    case 8: walk_k<8, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
-    case 7: walk_k<7, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
-    case 6: walk_k<6, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
-    case 5: walk_k<5, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
-    case 4: walk_k<4, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
-    case 3: walk_k<3, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
-    case 2: walk_k<2, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
-    case 1: walk_k<1, COMPACT, DUMP>(g, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 8: walk_k<8, COMPACT, DUMP>(tab, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 7: walk_k<7, COMPACT, DUMP>(tab, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 6: walk_k<6, COMPACT, DUMP>(tab, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 5: walk_k<5, COMPACT, DUMP>(tab, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 4: walk_k<4, COMPACT, DUMP>(tab, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 3: walk_k<3, COMPACT, DUMP>(tab, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 2: walk_k<2, COMPACT, DUMP>(tab, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
+    case 1: walk_k<1, COMPACT, DUMP>(tab, depth, lane_base, val_addr, val_stride, slot_ids, leaf_out); break;
     default: break;
     }
+}
+
+// The fields of a chunk header the kernel keeps in (scalar) registers.
+struct ChunkView {
+    uint32_t byte_off, bytes, n_trees, first_tree, slot_off;
+};
+
+__device__ __forceinline__ ChunkView load_chunk(const ChunkHdr *hdr_)
+{
+    auto hdr = FS_CONST(ChunkHdr, hdr_);
+    ChunkView v;
+    v.byte_off = hdr->byte_off;
+    v.bytes = hdr->bytes;
+    v.n_trees = hdr->n_trees;
+    v.first_tree = hdr->first_tree;
+    v.slot_off = hdr->slot_off;
+    return v;
 }
 
 template <bool DUMP>
@@ -134,7 +143,6 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
     const int tid = threadIdx.x;
     const int wave = uniform(tid >> 6), lane = tid & 63;
     const int T = d.lds_tiles;                  // tiles per workgroup
-    const int S = kLdsWaves / T;                // wavefronts sharing a tile
     const int my_tile = wave % T, my_slot = wave / T;
     const int n_tiles = (d.n_rows + 63) >> 6;
     const int tile_first = (blockIdx.x - d.lds_block0[mode]) * T;
@@ -151,7 +159,7 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
     // (Row-major input stages its rows at LDS offset 0 first, so there the chunk waits in
     // registers; column-blocked input lets chunk and tiles go straight from memory to LDS.)
     u32x4 pf[kPrefetchRegs];
-    ChunkHdr h = *FS_CONST(ChunkHdr, d.chunks);
+    ChunkView h = load_chunk(d.chunks);
     const bool direct = d.layout != FS_ROWMAJOR;
     {
         auto src = FS_GLOBAL(const u32x4, d.image + h.byte_off);
@@ -282,10 +290,10 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
     // prefetch registers they copy it alone, so a sum and the copy run side by side.
     const int n_copiers = kLdsThreads - 64 * T;
     for (int c = 0; c < n_chunks; ++c) {
-        ChunkHdr hn = h;
+        ChunkView hn = h;
         int n16_next = 0, cp_id = tid, cp_n = kLdsThreads;
         if (c + 1 < n_chunks) {                            // next chunk: global -> registers
-            hn = *FS_CONST(ChunkHdr, d.chunks + c + 1);
+            hn = load_chunk(d.chunks + c + 1);
             auto src = FS_GLOBAL(const u32x4, d.image + hn.byte_off);
             n16_next = (int)(hn.bytes >> 4);
             if (n16_next <= kPrefetchRegs * n_copiers) {
@@ -299,24 +307,31 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
             }
         }
         const int n = uniform((int)h.n_trees);
-        const int depth = uniform((int)h.depth);
         const uint32_t val0 = tile0 - (uint32_t)n * val_stride;   // packing keeps it above the image
         if (active) {
             const uint32_t val_addr = val0 + (uint32_t)my_tile * 256u + 4u * (uint32_t)lane;
             const uint16_t *ids = d.slot_ids + h.slot_off;
             uint16_t *leaf_out = leaf_row ? leaf_row + h.first_tree : nullptr;
-            // The chunk's trees are dealt out in `n_groups` runs of consecutive trees whose
-            // sizes differ by at most one (sizes <= 8); wavefront s of the tile takes runs
-            // s, s+S, ...
-            const int n_groups = S * ((n + 8 * S - 1) / (8 * S));
-            const int base = n / n_groups, rem = n - base * n_groups;
-            for (int j = my_slot; j < n_groups; j += S) {
-                const int g = j * base + min(j, rem);
-                const int count = base + (j < rem ? 1 : 0);
+            // this wavefront's runs of the chunk: record my_slot, then the records chained to it
+            uint32_t rec = (uint32_t)(kRunBytes * my_slot);
+            for (;;) {
+                uint32_t tab[8];
+                const uint32_t head = lds_u(rec);            // same address in every lane: broadcast
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    tab[k] = lds_u(rec + 4u + 4u * (uint32_t)k);
+                const uint32_t run = (uint32_t)uniform((int)head);
+                const int count = (int)(run & 0xFu), depth = (int)(run >> 16);
+                if (count == 0)
+                    break;                                   // idle slot
                 if (compact)
-                    walk_n<true, DUMP>(count, g, depth, lane_base, val_addr, val_stride, ids, leaf_out);
+                    walk_n<true, DUMP>(count, tab, depth, lane_base, val_addr, val_stride, ids, leaf_out);
                 else
-                    walk_n<false, DUMP>(count, g, depth, lane_base, val_addr, val_stride, ids, leaf_out);
+                    walk_n<false, DUMP>(count, tab, depth, lane_base, val_addr, val_stride, ids, leaf_out);
+                const uint32_t next = (run >> 4) & 0xFFFu;
+                if (next == 0)
+                    break;
+                rec = (uint32_t)kRunBytes * (next - 1u);
             }
         }
         __syncthreads();       // every walk of this chunk is done and its values are parked

@@ -372,6 +372,36 @@ def test_rank_coded_path_special_values_and_shallow_trees(api, oracle, tune):
         check_family(oracle, f, d)
 
 
+def test_trees_of_mixed_depth_walked_in_runs_of_their_own_depth(api, oracle):
+    """The LDS kernel walks a chunk's trees in runs, each to the depth of its deepest tree; with
+    many shallow trees the runs are formed by depth and dealt to the wavefronts by cost, with
+    few they stay in tree order.  Leaf ids, row scores and the sums (in tree order whatever the
+    walk order) must not notice: ensembles that mix stumps, single leaves and deep trees, a
+    chunk with more trees than one round of runs holds, and a model of single leaves only."""
+    def mixed(seed, n_trees, depths, n_features=164):
+        fam = W.make_small_family(seed=seed, n_programs=260, stmts=(1, 5), n_trees=n_trees, depth=1,
+                                  n_features=n_features, k=32, bias=0.125)
+        rng = np.random.default_rng(seed)
+        parts = [W.draw_model(rng, fam.features, 1, int(d), early_leaf_q=0.25 if d > 1 else 0.0)
+                 for d in rng.choice(depths, size=n_trees)]
+        off = np.concatenate([[0], np.cumsum([p.n_nodes for p in parts])]).astype(np.int32)
+        cat = lambda name: np.concatenate([getattr(p, name) for p in parts])
+        fam.model = W.Model(n_features, off, cat("split_feature"), cat("threshold"), cat("left"),
+                            cat("right"), cat("value"), 0.125)
+        return fam
+    fams = [mixed(701, 90, [0, 1, 1, 2, 9]),          # mostly shallow: runs formed by depth
+            mixed(702, 70, [7, 8, 8, 8, 8, 8, 1]),    # mostly deep: runs in tree order
+            mixed(703, 200, [1, 2, 3], 40),           # many small trees per chunk: several runs per wavefront
+            mixed(704, 30, [0])]                      # single leaves only
+    for layout in LAYOUTS:
+        devs = run_families(api, fams, layout)
+        for f, d in zip(fams, devs):
+            check_family(oracle, f, d)
+    devs = run_families(api, fams, api.FS_COLBLOCK64, want_rows=False, want_leaves=False)
+    for f, d in zip(fams, devs):
+        check_family(oracle, f, d)
+
+
 def test_models_outside_the_lds_formats_take_the_global_kernel(api, oracle):
     """More than 255 features, or trees too large for an LDS chunk: walked from global memory,
     in either layout."""
