@@ -62,6 +62,10 @@ def parse():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debug only)")
     ap.add_argument("--trees", type=int, default=None, help="override trees per family (debug only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--also", type=str, default=None,
+                    help="comma-separated workloads (0..4) to time briefly after the main one and "
+                         "report under `other_workloads` (default: 2 when the main one is configs[3], "
+                         "since configs[2] calls itself the bandwidth-roofline config; 'none' = skip)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for HBM counters)")
     return ap.parse_args()
@@ -131,6 +135,43 @@ def mean_path_length(case, devs, api, torch, sample_rows: int = 512):
         cnt += f.n_rows * m.n_trees
         lock += float(depth.max()) * f.n_rows * m.n_trees
     return (tot / max(1, cnt), lock / max(1, cnt), cnt)
+
+
+def quick_measure(cfg: int, seed: int, np, torch, api, W, steps: int = 10, warmup: int = 3) -> dict:
+    """A short timing of another workload with the same step (score + cut) and the same
+    accounting as the main one: ms per step, rows/s, traversal kernel time and HBM fraction."""
+    case = W.make_case(cfg, seed=seed)
+    devs = api.upload_case(case, layout=api.FS_COLBLOCK64)
+    fams = api.PreparedFamilies([d.family() for d in devs])
+    reqs = api.PreparedTopk([d.topk_request() for d in devs])
+    for _ in range(warmup):
+        api.fs_score_families(fams)
+        api.fs_topk(reqs)
+    torch.cuda.synchronize()
+    api.fs_profile_begin(8 * steps + 8)
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        api.fs_score_families(fams)
+        api.fs_topk(reqs)
+    e1.record()
+    torch.cuda.synchronize()
+    prof = api.fs_profile_end()
+    ms = e0.elapsed_time(e1) / steps
+    trav_ms = max(prof["traverse"][0], prof["rank_code"][0] + prof["traverse_rank"][0],
+                  prof["traverse_global"][0]) / steps
+    model_bytes = sum(8 * m.n_nodes for m in {id(f.model): f.model for f in case.families}.values())
+    alg_bytes = sum(f.n_rows * (f.model.n_features * 4 + 4) for f in case.families) + model_bytes
+    achieved = alg_bytes / (trav_ms * 1e-3) / 1e9 if trav_ms > 0 else 0.0
+    out = {"workload": "configs[%d] %s" % (cfg, case.name), "rows": case.n_rows, "steps": steps,
+           "ms_per_step": round(ms, 5), "rows_per_s": round(case.n_rows / (ms * 1e-3), 1),
+           "traverse_ms": round(trav_ms, 5), "achieved_gbs": round(achieved, 2),
+           "frac_of_hbm_peak": round(achieved / HBM_PEAK_GBS, 5),
+           "topk_us_per_family": round(prof["topk"][0] / steps * 1e3 / max(1, len(case.families)), 3)}
+    del devs, fams, reqs, case
+    torch.cuda.empty_cache()
+    return out
 
 
 def train_main(args, np, torch, api, W):
@@ -414,6 +455,15 @@ def main():
         "synthetic_loop": vloop,
         "frac_walked_of_synthetic_loop": round(walked_rate / vloop, 4) if vloop else None,
         "mean_path": round(mean_path, 3), "walked_levels": round(lock_path, 3)}
+
+    also = args.also
+    if also is None:
+        also = "2" if (args.config == 3 and not args.foresee and args.scale == 1.0 and args.trees is None) else "none"
+    if also != "none":
+        del devs, fams, reqs
+        torch.cuda.empty_cache()
+        out["other_workloads"] = [quick_measure(int(c), args.seed, np, torch, api, W)
+                                  for c in also.split(",") if c.strip() != ""]
 
     if not args.no_cpu_baseline:
         from oracle import oracle as O

@@ -68,7 +68,9 @@ template <int WIDTH>
 __device__ __forceinline__ void issue_read(uint32_t addr, u32x4 &dst)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
-    if (WIDTH == 4) {
+    if (WIDTH == 2) {
+        asm volatile("ds_read_u16 %0, %1" : "=v"(dst.x) : "v"(addr));
+    } else if (WIDTH == 4) {
         asm volatile("ds_read_b32 %0, %1" : "=v"(dst.x) : "v"(addr));
     } else if (WIDTH == 8) {
         u32x2 t;
@@ -131,7 +133,10 @@ static double run_lds(const char *name, Pattern pat, int waves, int lds_bytes, i
         for (int t = 0; t < threads; ++t) {
             const int lane = t & 63;
             uint32_t a = 0;
-            if (pat == kLaneBank) {
+            if (pat == kLaneBank && WIDTH == 2) {
+                // 16-bit values in pairs: lane l's word at row * 256 + 4 * l, either half of it
+                a = (uint32_t)(rnd() % (lds_bytes / 256)) * 256u + 4u * (uint32_t)lane + 2u * (rnd() & 1u);
+            } else if (pat == kLaneBank) {
                 const int rows = lds_bytes / (64 * WIDTH);
                 a = (uint32_t)(rnd() % rows) * 64u * WIDTH + (uint32_t)lane * WIDTH;
             } else if (pat == kBroadcast) {
@@ -261,6 +266,87 @@ static double run_visits(int waves, int depth, int n_cu, uint32_t *d_out)
     return clk;
 }
 
+// Synthetic walk over rank-coded data: 4-byte nodes in 1-based heap order without child
+// pointers (rank << 16 | offset of the feature in a tile), 16-bit feature ranks in pairs, K walks
+// per lane in lock-step -- the visit of the rank traversal kernel with nothing around it.
+template <int K>
+__global__ void __launch_bounds__(768) rank_visit_kernel(const uint32_t *__restrict__ image, int n_trees, int depth,
+                                                         int n_features, int rounds, uint32_t *out)
+{
+    extern __shared__ uint32_t lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tree_words = 2 << depth, image_words = n_trees * tree_words;
+    for (int i = tid; i < image_words; i += blockDim.x)
+        lds[i] = image[i];
+    const int tile0 = image_words * 4, cols = (n_features + 1) & ~1, tile_words = cols * 32;
+    for (int i = tid; i < 4 * tile_words; i += blockDim.x)            // four tiles
+        lds[tile0 / 4 + i] = (uint32_t)i * 2654435761u;
+    __syncthreads();
+    const uint32_t lane_base = (uint32_t)tile0 + (uint32_t)(wave & 3) * (uint32_t)tile_words * 4u + 4u * (uint32_t)lane;
+    uint32_t acc = 0;
+    for (int r = 0; r < rounds; ++r) {
+        uint32_t base[K], A[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            base[k] = (uint32_t)(((wave >> 2) * K + k + r) % n_trees) * (uint32_t)tree_words * 4u;
+            A[k] = base[k] + 4u;
+        }
+        for (int l = 0; l < depth; ++l) {
+            uint32_t nd[K], x[K];
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+                nd[k] = *(const uint32_t *)((const char *)lds + A[k]);
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+                x[k] = *(const uint16_t *)((const char *)lds + (nd[k] & 0xFFFFu) + lane_base);
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+                A[k] = (A[k] << 1) - base[k] + ((x[k] < (nd[k] >> 16)) ? 0u : 4u);
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            acc ^= A[k];
+    }
+    if (acc == 0x12345678u)
+        out[0] = acc;
+}
+
+template <int K>
+static double run_rank_visits(int depth, int n_trees, int n_cu, uint32_t *d_out)
+{
+    const int n_features = 164, lds_total = 160 * 1024, waves = 12;
+    const int tree_words = 2 << depth;
+    std::vector<uint32_t> img((size_t)n_trees * tree_words, 0);
+    for (int t = 0; t < n_trees; ++t)
+        for (int i = 1; i < tree_words; ++i) {
+            const uint32_t f = (uint32_t)(rnd() % n_features);
+            img[(size_t)t * tree_words + i] = ((rnd() & 0xFFFFu) << 16) | ((f >> 1) * 256u + (f & 1u) * 2u);
+        }
+    uint32_t *d_img;
+    CK(hipMalloc(&d_img, img.size() * 4));
+    CK(hipMemcpy(d_img, img.data(), img.size() * 4, hipMemcpyHostToDevice));
+    auto kern = rank_visit_kernel<K>;
+    CK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_total));
+    const int rounds = 400;
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0));
+    CK(hipEventCreate(&e1));
+    kern<<<n_cu, waves * 64, lds_total>>>(d_img, n_trees, depth, n_features, 4, d_out);
+    CK(hipDeviceSynchronize());
+    CK(hipEventRecord(e0));
+    kern<<<n_cu, waves * 64, lds_total>>>(d_img, n_trees, depth, n_features, rounds, d_out);
+    CK(hipEventRecord(e1));
+    CK(hipEventSynchronize(e1));
+    float ms;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    const double clk = ms * 1e-3 * 2.4e9 / ((double)rounds * K * depth * waves);
+    printf("  rank walk, depth %2d, %2d trees resident, 12 waves, %d walks per lane (%3d in flight per CU): "
+           "%6.2f clk per wavefront visit per CU -> %.3e visits/s\n", depth, n_trees, K, K * waves, clk,
+           64.0 * n_cu * 2.4e9 / clk);
+    CK(hipFree(d_img));
+    return clk;
+}
+
 int main()
 {
     hipDeviceProp_t p;
@@ -320,6 +406,12 @@ int main()
         c = run_lds<8, 8>("b64, random over 64 KB", kRandomAll, waves, 65536, 0, n_cu, d_out);
         if (c < b64_all) b64_all = c;
         run_lds<16, 8>("b128, lane in its own banks", kLaneBank, waves, 65536, 0, n_cu, d_out);
+        if (waves == 12) {
+            run_lds<2, 8>("u16, lane in its own bank (a rank-coded feature)", kLaneBank, waves, 65536, 0, n_cu, d_out);
+            run_lds<4, 8>("b32, random within 256 B (64 4-byte nodes)", kRandomSmall, waves, 65536, 256, n_cu, d_out);
+            run_lds<4, 8>("b32, random within 1 KB (256 4-byte nodes)", kRandomSmall, waves, 65536, 1024, n_cu, d_out);
+            run_lds<4, 8>("b32, random within 4 KB (1024 4-byte nodes)", kRandomSmall, waves, 65536, 4096, n_cu, d_out);
+        }
     }
 
     printf("Synthetic lock-step visit loop (8-byte nodes, fp32 tile, two tiles, whole LDS)\n");
@@ -330,13 +422,21 @@ int main()
         c = run_visits(waves, 6, n_cu, d_out);
         if (c < visit6) visit6 = c;
     }
+    printf("Synthetic walk over rank-coded data (4-byte heap nodes, 16-bit feature ranks, four tiles)\n");
+    run_rank_visits<2>(10, 8, n_cu, d_out);
+    const double rank3 = run_rank_visits<3>(10, 8, n_cu, d_out);
+    run_rank_visits<4>(10, 8, n_cu, d_out);
+    run_rank_visits<5>(10, 8, n_cu, d_out);
+    const double rank8 = run_rank_visits<8>(10, 8, n_cu, d_out);
+    run_rank_visits<8>(8, 32, n_cu, d_out);
     const double visit_peak = 64.0 * n_cu * 2.4e9 / (b64_cf + b32_cf);
     printf("JSON {\"hbm_read_stream_gbs\": %.0f, \"lds_b32_lane_bank_clk\": %.3f, \"lds_b64_lane_bank_clk\": %.3f, "
            "\"lds_b64_broadcast_clk\": %.3f, \"lds_b64_random_1k_clk\": %.3f, \"lds_b64_random_64k_clk\": %.3f, "
            "\"visit_loop_depth8_clk\": %.3f, \"visit_loop_depth6_clk\": %.3f, \"visit_peak_conflict_free\": %.4e, "
-           "\"visit_loop_measured\": %.4e, \"cus\": %d}\n",
+           "\"visit_loop_measured\": %.4e, \"rank_walk_depth10_k3_clk\": %.3f, \"rank_walk_depth10_k8_clk\": %.3f, "
+           "\"cus\": %d}\n",
            best_gbs, b32_cf, b64_cf, b64_bc, b64_small, b64_all, visit8, visit6, visit_peak,
-           64.0 * n_cu * 2.4e9 / visit8, n_cu);
+           64.0 * n_cu * 2.4e9 / visit8, rank3, rank8, n_cu);
     CK(hipFree(d_out));
     return 0;
 }
