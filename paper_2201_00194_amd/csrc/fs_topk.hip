@@ -90,6 +90,13 @@ topk_kernel(const TopkDesc *__restrict__ descs)
     const int per_wave = (((n + kTopkWaves - 1) / kTopkWaves) + 63) & ~63;
     const int w_begin = min(wave * per_wave, n), w_end = min(w_begin + per_wave, n);
 
+    // A wavefront whose slice is a single round of loads (requests of up to 8192 entries)
+    // fetches its keys once and keeps them in registers for all six sweeps below.
+    const bool cached = per_wave <= 64 * kTopkUnroll;
+    uint32_t key[kTopkUnroll];
+    if (cached && w_begin < w_end)
+        load_keys(score, w_begin, w_end, lane, key);
+
     // ---- 1. key of the kk-th best entry ----
     uint32_t prefix = 0, mask = 0;
     int need = kk;
@@ -100,8 +107,8 @@ topk_kernel(const TopkDesc *__restrict__ descs)
             __syncthreads();
             int run_digit = -1, run = 0;
             for (int base = w_begin; base < w_end; base += 64 * kTopkUnroll) {
-                uint32_t key[kTopkUnroll];
-                load_keys(score, base, w_end, lane, key);
+                if (!cached)
+                    load_keys(score, base, w_end, lane, key);
 #pragma unroll
                 for (int u = 0; u < kTopkUnroll; ++u) {
                     const bool valid = base + u * 64 + lane < w_end;
@@ -158,8 +165,8 @@ topk_kernel(const TopkDesc *__restrict__ descs)
     // ---- 2. collect, in index order: count per wavefront, scan, then place ----
     int my_gt = 0, my_eq = 0;
     for (int base = w_begin; base < w_end; base += 64 * kTopkUnroll) {
-        uint32_t key[kTopkUnroll];
-        load_keys(score, base, w_end, lane, key);
+        if (!cached)
+            load_keys(score, base, w_end, lane, key);
 #pragma unroll
         for (int u = 0; u < kTopkUnroll; ++u) {
             const bool valid = base + u * 64 + lane < w_end;
@@ -179,8 +186,8 @@ topk_kernel(const TopkDesc *__restrict__ descs)
     }
     const unsigned long long below = (1ull << lane) - 1ull;
     for (int base = w_begin; base < w_end; base += 64 * kTopkUnroll) {
-        uint32_t key[kTopkUnroll];
-        load_keys(score, base, w_end, lane, key);
+        if (!cached)
+            load_keys(score, base, w_end, lane, key);
 #pragma unroll
         for (int u = 0; u < kTopkUnroll; ++u) {
             const int i = base + u * 64 + lane;
