@@ -62,6 +62,9 @@ def parse():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debug only)")
     ap.add_argument("--trees", type=int, default=None, help="override trees per family (debug only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture one step (score + cut) into a HIP graph and time its replays "
+                         "(`graph_replay`): what a caller of a launch-bound workload would do")
     ap.add_argument("--also", type=str, default=None,
                     help="comma-separated workloads (0..4) to time briefly after the main one and "
                          "report under `other_workloads` (default: 2 when the main one is configs[3], "
@@ -455,6 +458,27 @@ def main():
         "synthetic_loop": vloop,
         "frac_walked_of_synthetic_loop": round(walked_rate / vloop, 4) if vloop else None,
         "mean_path": round(mean_path, 3), "walked_levels": round(lock_path, 3)}
+
+    if args.graph:
+        api.fs_workspace_reserve(api.fs_workspace_bytes(fams), api.fs_topk_workspace_bytes(reqs))
+        step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = torch.cuda.Event(enable_timing=True)
+        g1 = torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(args.steps):
+            graph.replay()
+        g1.record()
+        torch.cuda.synchronize()
+        g_ms = g0.elapsed_time(g1) / args.steps
+        out["graph_replay"] = {"ms_per_step": round(g_ms, 5), "rows_per_s": round(n_rows / (g_ms * 1e-3), 1)}
+        del graph
 
     also = args.also
     if also is None:

@@ -38,10 +38,19 @@
  *     synchronised, the old buffer freed and a larger one allocated.  A caller that has
  *     reserved enough (fs_workspace_bytes, fs_topk_workspace_bytes, fs_workspace_reserve)
  *     never gets here;
- *   - the call's descriptors (about 300 bytes per family, 56 per top-k workgroup) exceed
- *     the staging capacity (64 KB unless grown before): staging is re-allocated;
- *   - descriptors are staged through a ring of 8 pinned slots per device; the ninth
- *     submission waits until the first has finished on the device.
+ *   - the call's descriptors (232 bytes per family, 56 per top-k workgroup) exceed 16 KB
+ *     (about 70 families or 290 top-k workgroups).  Up to that size they travel as kernel
+ *     arguments; beyond it they are staged through a ring of 8 pinned slots per device: a
+ *     slot grows when it is too small, and the ninth such submission waits until the first
+ *     has finished on the device.
+ * A call that does neither only enqueues kernels on `stream`, so it may be recorded into a
+ * HIP graph (stream capture), provided every kernel form it uses has been launched once
+ * outside capture (a kernel's first launch on a device configures its LDS size).  A
+ * replayed graph reads the buffers and uses the descriptors of the captured call; it shares
+ * the library's descriptor buffers and scratch with later calls, so replays and other
+ * library calls must not overlap in time on different streams.  The graph also holds the
+ * address the scratch had at capture: reserve the largest scratch any later call on the
+ * device will need before capturing, so that it is never re-allocated under the graph.
  * fs_model_create, fs_trainer_create and the fs_trainer_* read-back calls synchronise
  * (stated where they are declared).
  */

@@ -47,11 +47,38 @@ struct Slot {
 // Two scratch regions per device, so that a scoring call and a top-k call never share bytes.
 enum { kScratchScore = 0, kScratchTopk = 1, kScratchRegions = 2 };
 
+// Descriptors of up to kInlineBytes travel as kernel arguments: a small kernel stores them into
+// a fixed device buffer (one per kind of call), in stream order in front of the kernels that read
+// them.  No pinned staging, no copy, no event and nothing to wait for, so such a call can also be
+// recorded into a HIP graph.  Longer descriptor arrays go through the ring of pinned slots.
+constexpr size_t kInlineBytes = 16384;
+constexpr size_t kBlobBytes = 3968;               // one kernel argument (the limit is 4 KB)
+enum { kDescScore = 0, kDescTopk = 1, kDescKinds = 2 };
+
 struct DeviceCtx {
     Slot slots[kSlots];
     int next = 0;
     float *scratch[kScratchRegions] = {nullptr, nullptr};
     size_t scratch_floats[kScratchRegions] = {0, 0};
+    void *inline_dev[kDescKinds] = {nullptr, nullptr};
+    void *inline_host[kDescKinds] = {nullptr, nullptr};
+};
+
+struct DescBlob {
+    uint32_t words[kBlobBytes / 4];
+};
+
+__global__ void __launch_bounds__(256) desc_store_kernel(DescBlob blob, uint32_t *dst, int n_words)
+{
+    for (int i = threadIdx.x; i < n_words; i += blockDim.x)
+        dst[i] = blob.words[i];
+}
+
+// Where a call builds its descriptors (host) and where the kernels read them (dev).
+struct DescBuf {
+    void *host = nullptr;
+    void *dev = nullptr;
+    Slot *slot = nullptr;                          // null: the inline path
 };
 
 static std::mutex g_mu;
@@ -109,6 +136,66 @@ static int ensure_scratch(DeviceCtx *ctx, int which, size_t floats, bool exact =
     size_t want = exact ? floats : floats + floats / 4 + 1024;
     FS_HIP(hipMalloc((void **)&ctx->scratch[which], want * sizeof(float)));
     ctx->scratch_floats[which] = want;
+    return FS_OK;
+}
+
+static int ensure_inline(DeviceCtx *ctx, int kind)
+{
+    if (!ctx->inline_dev[kind])
+        FS_HIP(hipMalloc(&ctx->inline_dev[kind], kInlineBytes));
+    if (!ctx->inline_host[kind]) {
+        ctx->inline_host[kind] = malloc(kInlineBytes);
+        if (!ctx->inline_host[kind])
+            return fail(FS_ENOMEM, "host allocation failed");
+    }
+    return FS_OK;
+}
+
+static int acquire_desc(DeviceCtx *ctx, int kind, size_t bytes, DescBuf *out)
+{
+    *out = DescBuf();
+    if (bytes <= kInlineBytes) {
+        int rc = ensure_inline(ctx, kind);
+        if (rc != FS_OK)
+            return rc;
+        out->host = ctx->inline_host[kind];
+        out->dev = ctx->inline_dev[kind];
+        return FS_OK;
+    }
+    int rc = acquire_slot(ctx, bytes, &out->slot);
+    if (rc != FS_OK)
+        return rc;
+    out->host = out->slot->h_buf;
+    out->dev = out->slot->d_buf;
+    return FS_OK;
+}
+
+// Descriptors to the device, in stream order in front of the kernels that follow.
+static int commit_desc(const DescBuf &db, size_t bytes, hipStream_t stream)
+{
+    if (db.slot) {
+        FS_HIP(hipMemcpyAsync(db.dev, db.host, bytes, hipMemcpyHostToDevice, stream));
+        db.slot->used = true;
+        return FS_OK;
+    }
+    for (size_t at = 0; at < bytes; at += kBlobBytes) {
+        const size_t n = bytes - at < kBlobBytes ? bytes - at : kBlobBytes;
+        DescBlob blob;
+        memcpy(blob.words, (const char *)db.host + at, n);
+        hipLaunchKernelGGL(desc_store_kernel, dim3(1), dim3(256), 0, stream, blob,
+                           (uint32_t *)((char *)db.dev + at), (int)((n + 3) / 4));
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return fail_hip(e, "desc_store_kernel launch");
+    }
+    return FS_OK;
+}
+
+// After the last kernel of the call: the slot may be reused once this point is reached.
+static int finish_desc(const DescBuf &db, hipStream_t stream)
+{
+    if (db.slot)
+        FS_HIP(hipEventRecord(db.slot->done, stream));
     return FS_OK;
 }
 
@@ -307,6 +394,8 @@ extern "C" int fs_workspace_reserve(size_t score_bytes, size_t topk_bytes)
     rc = ensure_scratch(ctx, kScratchScore, (score_bytes + 3) / 4, true);
     if (rc == FS_OK)
         rc = ensure_scratch(ctx, kScratchTopk, (topk_bytes + 3) / 4, true);
+    for (int kind = 0; kind < kDescKinds && rc == FS_OK; ++kind)
+        rc = ensure_inline(ctx, kind);
     for (int i = 0; i < kSlots && rc == FS_OK; ++i) {       // staging of every slot of the ring
         Slot *s = &ctx->slots[i];
         if (!s->done)
@@ -345,11 +434,11 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
     if (rc != FS_OK)
         return rc;
 
-    Slot *slot = nullptr;
-    rc = acquire_slot(ctx, sizeof(FamDesc) * (size_t)n_families, &slot);
+    DescBuf db;
+    rc = acquire_desc(ctx, kDescScore, sizeof(FamDesc) * (size_t)n_families, &db);
     if (rc != FS_OK)
         return rc;
-    FamDesc *h = (FamDesc *)slot->h_buf;
+    FamDesc *h = (FamDesc *)db.host;
     int64_t trav_blocks = 0, seg_blocks = 0, lds_blocks[kLdsModes] = {0, 0};
     int64_t rk_blocks = 0, bin_blocks = 0, retile_blocks = 0;
     bool rk_dump = false;
@@ -461,11 +550,10 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         retile_blocks >= ((int64_t)1 << 31))
         return fail(FS_EUNSUPPORTED, "fs_score_families: too much work for one submission");
 
-    FS_HIP(hipMemcpyAsync(slot->d_buf, slot->h_buf, sizeof(FamDesc) * (size_t)n_families,
-                          hipMemcpyHostToDevice, stream));
-    slot->used = true;
-    const FamDesc *d_desc = (const FamDesc *)slot->d_buf;
-    rc = FS_OK;
+    rc = commit_desc(db, sizeof(FamDesc) * (size_t)n_families, stream);
+    if (rc != FS_OK)
+        return rc;
+    const FamDesc *d_desc = (const FamDesc *)db.dev;
     if (retile_blocks > 0) {
         prof_start(kKernPack, stream);
         rc = launch_retile(d_desc, n_families, (int)retile_blocks, stream);
@@ -498,12 +586,8 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
         rc = launch_segsum(d_desc, n_families, (int)seg_blocks, stream);
         prof_stop(stream);
     }
-    hipError_t e = hipEventRecord(slot->done, stream);
-    if (rc != FS_OK)
-        return rc;
-    if (e != hipSuccess)
-        return fail_hip(e, "hipEventRecord");
-    return FS_OK;
+    const int rc2 = finish_desc(db, stream);
+    return rc != FS_OK ? rc : rc2;
 }
 
 // ---- top-k -------------------------------------------------------------------------------------
@@ -613,13 +697,13 @@ extern "C" int fs_topk(int32_t n_requests, const fs_topk_req *reqs, void *stream
     const size_t merge_off = (desc_bytes + 15) & ~(size_t)15;
     const size_t path_off = (merge_off + sizeof(TopkMergeDesc) * n_merge + 15) & ~(size_t)15;
     const size_t total_bytes = path_off + sizeof(TopkPairDesc) * n_pairs_total;
-    Slot *slot = nullptr;
-    rc = acquire_slot(ctx, total_bytes, &slot);
+    DescBuf db;
+    rc = acquire_desc(ctx, kDescTopk, total_bytes, &db);
     if (rc != FS_OK)
         return rc;
-    TopkDesc *h = (TopkDesc *)slot->h_buf;
-    TopkMergeDesc *hm = (TopkMergeDesc *)((char *)slot->h_buf + merge_off);
-    TopkPairDesc *hp = (TopkPairDesc *)((char *)slot->h_buf + path_off);
+    TopkDesc *h = (TopkDesc *)db.host;
+    TopkMergeDesc *hm = (TopkMergeDesc *)((char *)db.host + merge_off);
+    TopkPairDesc *hp = (TopkPairDesc *)((char *)db.host + path_off);
     unsigned long long *comp = (unsigned long long *)ctx->scratch[kScratchTopk];
     // merge-path descriptors are stored level by level: first count the pairs of every level
     constexpr int kMaxLevels = 8;
@@ -720,23 +804,20 @@ extern "C" int fs_topk(int32_t n_requests, const fs_topk_req *reqs, void *stream
     }
     if ((size_t)(comp - (unsigned long long *)ctx->scratch[kScratchTopk]) > comp_total || b != n_blocks || m != n_merge)
         return fail(FS_EDEVICE, "fs_topk: internal plan mismatch");
-    FS_HIP(hipMemcpyAsync(slot->d_buf, slot->h_buf, total_bytes, hipMemcpyHostToDevice, stream));
-    slot->used = true;
-    prof_start(kKernTopk, stream);
-    rc = launch_topk((const TopkDesc *)slot->d_buf, (int)n_blocks, max_k, stream);
-    if (rc == FS_OK && n_merge)
-        rc = launch_topk_merge((const TopkMergeDesc *)((const char *)slot->d_buf + merge_off),
-                               (int)n_merge, max_comp, stream);
-    for (int lv = 0; lv < n_levels && rc == FS_OK; ++lv)
-        rc = launch_topk_pairs((const TopkPairDesc *)((const char *)slot->d_buf + path_off) + level_at[lv],
-                               (int)level_pairs[lv], level_entries[lv], stream);
-    prof_stop(stream);
-    hipError_t e = hipEventRecord(slot->done, stream);
+    rc = commit_desc(db, total_bytes, stream);
     if (rc != FS_OK)
         return rc;
-    if (e != hipSuccess)
-        return fail_hip(e, "hipEventRecord");
-    return FS_OK;
+    prof_start(kKernTopk, stream);
+    rc = launch_topk((const TopkDesc *)db.dev, (int)n_blocks, max_k, stream);
+    if (rc == FS_OK && n_merge)
+        rc = launch_topk_merge((const TopkMergeDesc *)((const char *)db.dev + merge_off),
+                               (int)n_merge, max_comp, stream);
+    for (int lv = 0; lv < n_levels && rc == FS_OK; ++lv)
+        rc = launch_topk_pairs((const TopkPairDesc *)((const char *)db.dev + path_off) + level_at[lv],
+                               (int)level_pairs[lv], level_entries[lv], stream);
+    prof_stop(stream);
+    const int rc2 = finish_desc(db, stream);
+    return rc != FS_OK ? rc : rc2;
 }
 
 // ---- layout helper -----------------------------------------------------------------------------

@@ -114,3 +114,45 @@ def test_tuning_overrides_are_explicit_and_reset(api, tune):
     assert api.fs_tune_get(api.FS_TUNE_RANK) == -1
     with pytest.raises(api.FsError):
         api.fs_tune_set(99, 1)
+
+
+def test_small_calls_replay_from_a_hip_graph(api, oracle):
+    """A scoring call and a cut whose descriptors travel as kernel arguments and whose scratch was
+    reserved only enqueue kernels, so they can be captured into a graph.  The graph is replayed
+    several times on changed features, with eager library work and synchronisations in between,
+    and every replay is checked against the oracle."""
+    import torch
+    fams = families()
+    devs = [api.DeviceFamily(f) for f in fams]
+    prepared = api.PreparedFamilies([d.family() for d in devs])
+    reqs = api.PreparedTopk([d.topk_request() for d in devs])
+    rng = np.random.default_rng(17)
+    other = torch.from_numpy(rng.standard_normal(50000).astype(np.float32)).cuda()
+    o_idx = torch.zeros(100, dtype=torch.int32, device="cuda")
+    other_req = api.PreparedTopk([api.TopkRequest(other, 50000, 100, o_idx, None)])
+    # a graph keeps the scratch addresses it was captured with: reserve what any later call needs
+    api.fs_workspace_reserve(api.fs_workspace_bytes(prepared),
+                             max(api.fs_topk_workspace_bytes(reqs), api.fs_topk_workspace_bytes(other_req)))
+    api.fs_score_families(prepared)               # every kernel form once outside capture
+    api.fs_topk(reqs)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        api.fs_score_families(prepared)
+        api.fs_topk(reqs)
+    for replay in range(4):
+        for f, d in zip(fams, devs):              # new candidates in the same buffers
+            f.features[:] = W.draw_features(rng, f.n_rows, 0.3, n_features=f.features.shape[1])
+            x = torch.from_numpy(f.features).cuda()
+            api.fs_pack_colblock64(x, f.n_rows, f.features.shape[1], out=d.features)
+            d.prog_score.fill_(float("nan"))
+            d.topk_idx.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for f, d in zip(fams, devs):
+            same(d, f, *expect(oracle, f))
+        # eager work between the replays: another cut (its descriptors overwrite the graph's)
+        api.fs_topk(other_req)
+        torch.cuda.synchronize()
+        assert np.array_equal(o_idx.cpu().numpy(), oracle.topk(other.cpu().numpy(), 100)[0])
