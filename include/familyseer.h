@@ -286,7 +286,9 @@ enum {
     FS_TUNE_TRAIN_SLAB_ROWS = 5,  /* 64..65536: rows per histogram slab                             */
     FS_TUNE_TRAIN_SORT = 6,       /* 0: never regroup rows by node, 1: whenever possible            */
     FS_TUNE_TRAIN_PACKED = 7,     /* 0: separate 64-bit gradient / curvature sums only              */
-    FS_TUNE_OPTIONS = 8
+    FS_TUNE_LDS_GROUPS = 8,       /* 1..16: tile groups a workgroup of the LDS traversal takes in a
+                                     row (automatic: 1..4 by the length of the launch)             */
+    FS_TUNE_OPTIONS = 9
 };
 int fs_tune_set(int32_t option, int32_t value);
 int32_t fs_tune_get(int32_t option);   /* current override, -1 = automatic */

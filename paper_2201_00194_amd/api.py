@@ -85,7 +85,8 @@ _lib.fs_tune_set.argtypes = [ctypes.c_int32, ctypes.c_int32]
 _lib.fs_tune_get.restype = ctypes.c_int32
 _lib.fs_tune_get.argtypes = [ctypes.c_int32]
 (FS_TUNE_LDS_TILES, FS_TUNE_LDS_MODE, FS_TUNE_RANK, FS_TUNE_RANK_TILES, FS_TUNE_VERBOSE,
- FS_TUNE_TRAIN_SLAB_ROWS, FS_TUNE_TRAIN_SORT, FS_TUNE_TRAIN_PACKED) = range(8)
+ FS_TUNE_TRAIN_SLAB_ROWS, FS_TUNE_TRAIN_SORT, FS_TUNE_TRAIN_PACKED, FS_TUNE_LDS_GROUPS) = range(9)
+FS_TUNE_OPTIONS = 9
 
 _lib.fs_profile_begin.restype = ctypes.c_int
 _lib.fs_profile_begin.argtypes = [ctypes.c_int32]

@@ -219,7 +219,19 @@ __host__ __device__ inline uint32_t rank_feature_offset(int f) { return (uint32_
 int launch_traverse_global(const FamDesc *d_desc, int n_families, int total_blocks,
                            hipStream_t stream);
 int launch_traverse_lds(const FamDesc *d_desc, int n_families, int mode, int total_blocks,
-                        bool dump, hipStream_t stream);
+                        int groups_per_wg, bool dump, hipStream_t stream);
+// Tile groups one workgroup of the LDS traversal takes in a row; host (workgroup counts) and
+// kernel agree on it through this function.  From its second group on a workgroup receives the
+// tiles through registers, kLdsTileRegs 16-byte pieces per thread, so `want` only holds for
+// column-blocked input whose `tiles` tiles fit there; other families get one group per workgroup.
+constexpr int kLdsTileRegs = 7;
+__host__ __device__ inline int lds_groups_per_wg(int layout, int n_features, int tiles, int threads,
+                                                 int want)
+{
+    if (layout != FS_COLBLOCK64 || tiles * n_features * 16 > kLdsTileRegs * threads)
+        return 1;
+    return want < 1 ? 1 : want;
+}
 int launch_rank_code(const FamDesc *d_desc, int n_families, int total_blocks, hipStream_t stream);
 int launch_traverse_rank(const FamDesc *d_desc, int n_families, int total_blocks, bool dump,
                          hipStream_t stream);

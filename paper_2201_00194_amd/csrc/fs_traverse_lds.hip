@@ -18,6 +18,11 @@
 // being walked.  A chunk's trees are cut into runs of similar depth that are dealt to the
 // wavefronts (run records at the head of the chunk image).
 //
+// In a long launch a workgroup takes several consecutive groups of tiles (MULTI): only the
+// first group's tiles are fetched with nothing else to do; the next group's tiles, and the
+// model's first chunk again, are fetched into registers while the last chunk of the current
+// group is being walked, and stored to LDS once those walks are done.
+//
 // LDS map:  [0, chunk bytes)                    current model chunk (node offsets are
 //                                               absolute LDS addresses)
 //           [tile0 - trees*tiles*256, tile0)    leaf values [tree][tile][lane]
@@ -125,9 +130,9 @@ __device__ __forceinline__ ChunkView load_chunk(const ChunkHdr *hdr_)
     return v;
 }
 
-template <bool DUMP>
+template <bool DUMP, bool MULTI>
 __global__ void __launch_bounds__(64 * kLdsMaxWaves)
-traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
+traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode, int groups_per_wg)
 {
     const int kLdsThreads = blockDim.x;
     const int kLdsWaves = kLdsThreads >> 6;
@@ -145,21 +150,30 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
     const int T = d.lds_tiles;                  // tiles per workgroup
     const int my_tile = wave % T, my_slot = wave / T;
     const int n_tiles = (d.n_rows + 63) >> 6;
-    const int tile_first = (blockIdx.x - d.lds_block0[mode]) * T;
-    const int tiles_here = min(T, n_tiles - tile_first);
-    const bool active = my_tile < tiles_here;
     const int F = d.n_features;
+    // A workgroup takes several consecutive tile groups when the next group's tiles can wait in
+    // registers (column-blocked input whose tiles fit kLdsTileRegs pieces per thread): they are
+    // fetched while the last chunk of the current group is walked.
+    const int n_groups = (n_tiles + T - 1) / T;
+    const int G = MULTI ? lds_groups_per_wg(d.layout, F, T, kLdsThreads, groups_per_wg) : 1;
+    const int g_first = (blockIdx.x - d.lds_block0[mode]) * G;
+    const int g_end = min(g_first + G, n_groups);
     const uint32_t tile_bytes = (uint32_t)(F + 1) * 256u;
     const uint32_t tile0 = (uint32_t)d.lds_tile0;
     const uint32_t lane_base = tile0 + (uint32_t)my_tile * tile_bytes + 4u * (uint32_t)lane;
+    const int per_tile = F * 16;                           // 16-byte pieces per tile
+    u32x4 pf[kPrefetchRegs];
+    ChunkView h = load_chunk(d.chunks);
+  {
+    // the workgroup's first group: chunk and tiles straight from memory
+    const int tile_first = g_first * T;
+    const int tiles_here = min(T, n_tiles - tile_first);
 
     // ---- first chunk: global -> registers (lands while the tiles are being fetched) ----
     // Loads are unconditional with clamped indices (no branches between them, so they all go
     // out back to back); only the LDS writes are predicated.
     // (Row-major input stages its rows at LDS offset 0 first, so there the chunk waits in
     // registers; column-blocked input lets chunk and tiles go straight from memory to LDS.)
-    u32x4 pf[kPrefetchRegs];
-    ChunkView h = load_chunk(d.chunks);
     const bool direct = d.layout != FS_ROWMAJOR;
     {
         auto src = FS_GLOBAL(const u32x4, d.image + h.byte_off);
@@ -227,7 +241,6 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
     } else {
         // consecutive tiles are one contiguous run in HBM
         auto src = FS_GLOBAL(const u32x4, d.features + (int64_t)tile_first * F * 64);
-        const int per_tile = F * 16;                       // 16-byte pieces per tile
         const int n16 = tiles_here * per_tile;
         if ((per_tile & 63) == 0) {
             // F % 4 == 0: every group of 64 pieces lies inside one tile
@@ -274,7 +287,13 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
         }
     }
     __syncthreads();
+  }
 
+  // Later groups of the workgroup arrive through registers (tp and pf below).
+  for (int grp = g_first; grp < g_end; ++grp) {
+    const int tile_first = grp * T;
+    const int tiles_here = min(T, n_tiles - tile_first);
+    const bool active = my_tile < tiles_here;
     const int r = (tile_first + my_tile) * 64 + lane;
     float acc = d.bias;
     uint16_t *leaf_row = nullptr;
@@ -290,10 +309,17 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
     // prefetch registers they copy it alone, so a sum and the copy run side by side.
     const int n_copiers = kLdsThreads - 64 * T;
     for (int c = 0; c < n_chunks; ++c) {
+        // After the last chunk of a group that is not the workgroup's last, the next group's
+        // tiles travel the same way as the next chunk (and the first chunk comes back when the
+        // model has more than one).
+        const bool last = c + 1 == n_chunks;
+        const bool wrap = MULTI && last && grp + 1 < g_end;
+        const bool fetch = !last || (wrap && n_chunks > 1);
         ChunkView hn = h;
         int n16_next = 0, cp_id = tid, cp_n = kLdsThreads;
-        if (c + 1 < n_chunks) {                            // next chunk: global -> registers
-            hn = load_chunk(d.chunks + c + 1);
+        u32x4 tp[kLdsTileRegs];
+        if (fetch) {                                       // next chunk: global -> registers
+            hn = load_chunk(d.chunks + (last ? 0 : c + 1));
             auto src = FS_GLOBAL(const u32x4, d.image + hn.byte_off);
             n16_next = (int)(hn.bytes >> 4);
             if (n16_next <= kPrefetchRegs * n_copiers) {
@@ -305,6 +331,14 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
                 for (int j = 0; j < kPrefetchRegs; ++j)
                     pf[j] = src[min(cp_id + j * cp_n, n16_next - 1)];
             }
+        }
+        if (wrap) {
+            const int next_first = (grp + 1) * T;
+            const int n16t = min(T, n_tiles - next_first) * per_tile;
+            auto src = FS_GLOBAL(const u32x4, d.features + (int64_t)next_first * F * 64);
+#pragma unroll
+            for (int q = 0; q < kLdsTileRegs; ++q)
+                tp[q] = src[min(tid + q * kLdsThreads, n16t - 1)];
         }
         const int n = uniform((int)h.n_trees);
         const uint32_t val0 = tile0 - (uint32_t)n * val_stride;   // packing keeps it above the image
@@ -339,17 +373,30 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
             const uint32_t va = val0 + (uint32_t)my_tile * 256u + 4u * (uint32_t)lane;
             ordered_add_n(acc, va, val_stride, n);
         }
-        if (c + 1 < n_chunks) {
+        if (fetch || wrap) {
             // The next image may be long enough to reach into the value rows that are being
             // summed right now (only when chunk sizes differ a lot): then wait for the readers.
-            if (16u * (uint32_t)n16_next > val0)
+            if (fetch && 16u * (uint32_t)n16_next > val0)
                 __syncthreads();
-            if (cp_id >= 0) {
+            if (fetch && cp_id >= 0) {
 #pragma unroll
                 for (int j = 0; j < kPrefetchRegs; ++j) {
                     const int i = cp_id + j * cp_n;
                     if (i < n16_next)
                         lds_store_u4(16u * (uint32_t)i, pf[j]);
+                }
+            }
+            if (wrap) {                                    // every walk of this group is done
+                const int n16t = min(T, n_tiles - (grp + 1) * T) * per_tile;
+#pragma unroll
+                for (int q = 0; q < kLdsTileRegs; ++q) {
+                    const int i = tid + q * kLdsThreads;
+                    if (i < n16t) {
+                        // piece i of tile t sits 16 * i + 256 * t above tile0 (the NaN column of
+                        // every tile before it); at most kLdsMaxTiles = 3 tiles, so no division
+                        const int t = (i >= per_tile ? 1 : 0) + (i >= 2 * per_tile ? 1 : 0);
+                        lds_store_u4(tile0 + 16u * (uint32_t)i + 256u * (uint32_t)t, tp[q]);
+                    }
                 }
             }
             __syncthreads();
@@ -358,37 +405,36 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode)
     }
     if (active && my_slot == 0 && r < d.n_rows)
         FS_GLOBAL(float, d.row_score)[r] = acc;
+  }   // tile groups of this workgroup
 }
 
 int launch_traverse_lds(const FamDesc *d_desc, int n_families, int mode, int total_blocks,
-                        bool dump, hipStream_t stream)
+                        int groups_per_wg, bool dump, hipStream_t stream)
 {
     const int kLdsBytes = kLdsModeBytes[mode];
     const int kLdsThreads = 64 * kLdsModeWaves[mode];
-    static bool configured[16][2] = {};
+    static bool configured[16][4] = {};
     int dev = 0;
     FS_HIP(hipGetDevice(&dev));
-    const void *fn = dump ? (const void *)traverse_lds_kernel<true>
-                          : (const void *)traverse_lds_kernel<false>;
-    if (dev < 0 || dev >= 16 || !configured[dev][dump ? 1 : 0]) {
+    const bool multi = groups_per_wg > 1;
+    auto kernel = dump ? (multi ? traverse_lds_kernel<true, true> : traverse_lds_kernel<true, false>)
+                       : (multi ? traverse_lds_kernel<false, true> : traverse_lds_kernel<false, false>);
+    const int form = (dump ? 2 : 0) + (multi ? 1 : 0);
+    if (dev < 0 || dev >= 16 || !configured[dev][form]) {
         // The kernel addresses LDS absolutely from 0, so it must own all of it: no static LDS
         // (nothing the compiler may have moved there either).
         hipFuncAttributes attr;
-        FS_HIP(hipFuncGetAttributes(&attr, fn));
+        FS_HIP(hipFuncGetAttributes(&attr, (const void *)kernel));
         if (attr.sharedSizeBytes != 0)
             return fail(FS_EDEVICE, "traverse_lds_kernel was built with %zu bytes of static LDS",
                         (size_t)attr.sharedSizeBytes);
-        FS_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+        FS_HIP(hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                    kLdsModeBytes[kLdsModes - 1]));
         if (dev >= 0 && dev < 16)
-            configured[dev][dump ? 1 : 0] = true;
+            configured[dev][form] = true;
     }
-    if (dump)
-        hipLaunchKernelGGL(traverse_lds_kernel<true>, dim3(total_blocks), dim3(kLdsThreads),
-                           kLdsBytes, stream, d_desc, n_families, mode);
-    else
-        hipLaunchKernelGGL(traverse_lds_kernel<false>, dim3(total_blocks), dim3(kLdsThreads),
-                           kLdsBytes, stream, d_desc, n_families, mode);
+    hipLaunchKernelGGL(kernel, dim3(total_blocks), dim3(kLdsThreads), kLdsBytes, stream, d_desc,
+                       n_families, mode, groups_per_wg);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return fail_hip(e, "traverse_lds_kernel launch");

@@ -402,6 +402,36 @@ def test_trees_of_mixed_depth_walked_in_runs_of_their_own_depth(api, oracle):
         check_family(oracle, f, d)
 
 
+@pytest.mark.parametrize("groups", [2, 3, 4, 16])
+def test_workgroups_that_take_several_tile_groups(api, oracle, tune, groups):
+    """In a long launch a workgroup of the LDS kernel walks several consecutive groups of tiles
+    and receives all but the first through registers while it is still walking.  Forced here on
+    small inputs: group counts that the workgroups do not divide evenly, a last group with a
+    single tile and a ragged last tile, one-chunk and many-chunk models, a family shorter than
+    one workgroup's share, leaf ids on and off, and row-major input beside it (one group per
+    workgroup there).  Every output must equal the oracle's, as with one group per workgroup."""
+    tune(api.FS_TUNE_LDS_GROUPS, groups)
+    fams = [W.make_small_family(seed=811, n_programs=700, stmts=(1, 7), n_trees=24, depth=4,
+                                early_leaf_q=0.3, k=40, bias=-0.25),       # one chunk
+            W.make_small_family(seed=812, n_programs=523, stmts=(2, 6), n_trees=150, depth=6,
+                                early_leaf_q=0.25, k=64),                   # several chunks
+            W.make_small_family(seed=813, n_programs=40, stmts=(1, 4), n_trees=150, depth=6,
+                                early_leaf_q=0.25, k=8),                    # fewer groups than a share
+            W.make_small_family(seed=814, n_programs=301, stmts=(3, 3), n_trees=9, depth=2, k=301)]
+    assert any(((f.n_rows + 63) // 64) % 2 == 1 for f in fams)     # a last group of one tile
+    for layout in LAYOUTS:
+        devs = run_families(api, fams, layout)
+        for f, d in zip(fams, devs):
+            check_family(oracle, f, d)
+    devs = run_families(api, fams, api.FS_COLBLOCK64, want_rows=False, want_leaves=False)
+    for f, d in zip(fams, devs):
+        check_family(oracle, f, d)
+    case = W.make_case(3, seed=2, scale=0.02, trees=50)
+    devs = run_families(api, case.families, api.FS_COLBLOCK64, want_leaves=False)
+    for f, d in zip(case.families, devs):
+        check_family(oracle, f, d, check_leaves=False)
+
+
 def test_models_outside_the_lds_formats_take_the_global_kernel(api, oracle):
     """More than 255 features, or trees too large for an LDS chunk: walked from global memory,
     in either layout."""
