@@ -31,6 +31,7 @@
 
 #include "familyseer_train.h"
 #include "fs_internal.h"
+#include "fs_lds.h"
 
 namespace fs {
 
@@ -284,7 +285,7 @@ __device__ __forceinline__ long long shfl_up_ll(long long v, int off) { return _
 // coming later it never wins.  (A row's curvature is at least 1, so a bin is empty exactly when
 // its H is 0.)  Deep in a tree a node holds fewer rows than a feature has bins and most cuts
 // drop out this way; when at most 64 are left they are handed out one per lane through
-// `scratch` (this wavefront's own kCutScratchBytes of LDS), so that the wavefront pays for one
+// `scratch` (kCutScratchBytes of LDS that only this wavefront touches), so that the wavefront pays for one
 // round of double-precision divisions instead of four.  Measured: the cut search is two thirds
 // of the histogram kernel's time at depth 10.
 constexpr int kCutScratchBytes = 64 * (8 + 8 + 4);
@@ -430,56 +431,86 @@ __device__ __forceinline__ void wave_best_cut(const TrainDesc &d, const Params &
 // which train_grad_kernel leaves in abs_q, stays below 2^(63-hb).  Wide: G and H in 64 bits
 // each, always safe; a workgroup launched for the packed form falls back to it, its nodes in
 // two halves, when the gradients of its trainer are too large.  Both are exact integer sums.
+constexpr int kHistFeats = 4;           // features per workgroup: one 32-bit word of bins per row
 constexpr int kHistSlotsWide = 8;       // 8 nodes x 4 features x 256 bins x 16 B = 128 KB
 constexpr int kHistSlotsPacked = 16;    // 16 nodes x 4 features x 256 bins x 8 B = 128 KB
-constexpr int kHistCutScratch = (kHistThreads / 64) * kCutScratchBytes;   // 20 KB in front of them
+// Behind the histograms: where the adds of rows that do not count land (rows past the end, of
+// other nodes, or in the feature's most frequent bin), one word per lane and feature, so that
+// the row loop has no branches.
+constexpr int kHistTrashWords = (kHistFeats - 1) * kBins + 64;
+static_assert(kBins * 8 >= kCutScratchBytes, "the cut search borrows its pair's own histogram");
 
 // One run of `slots` nodes, the first being number `abs0` of its level (heap index node0).
 template <bool PACKED>
 __device__ __forceinline__ void hist_run(const TrainDesc &d, const Params &prm,
                                          unsigned long long *lds_hist, int node0, int abs0, int slots,
-                                         int row0, int row1, int f0, int nf, const int (&hot)[4],
+                                         int row0, int row1, int f0, int nf, const int (&hot)[kHistFeats],
                                          const uint32_t *__restrict__ words,
                                          const uint16_t *__restrict__ node_of,
-                                         const int2 *__restrict__ qh_of, int n_slabs, int hb,
-                                         unsigned char *cut_scratch)
+                                         const int2 *__restrict__ qh_of, int n_slabs, int hb)
 {
-    const int pairs = slots * 4;
+    const int pairs = slots * kHistFeats;
     unsigned long long *lds_h = lds_hist + pairs * kBins;       // wide form only
     for (int i = threadIdx.x; i < pairs * kBins * (PACKED ? 1 : 2); i += kHistThreads)
         lds_hist[i] = 0ull;
     __syncthreads();
-    constexpr int kUnroll = 8;
-    for (int base = row0 + threadIdx.x; base < row1; base += kHistThreads * kUnroll) {
-        int slot[kUnroll];
-        uint32_t w[kUnroll];
-        int2 qh[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {                      // loads first
-            const int r = min(base + u * kHistThreads, row1 - 1);
-            slot[u] = (int)node_of[r] - node0;
-            w[u] = words[r];
-            qh[u] = qh_of[r];
-        }
+    // Rows in batches of kUnroll per thread.  The loads of the next batch are issued before the
+    // atomics of the current one, so that their latency passes while the LDS works.  (Indices
+    // are clamped to the last row: a batch past the end loads that row again and counts nothing.)
+    // The loop is bound by instruction issue, so it is kept free of branches: an add that does
+    // not count goes to the lane's own trash word instead.
+    constexpr int kUnroll = 4;
+    const int trash = pairs * kBins * (PACKED ? 1 : 2) + (threadIdx.x & 63);
+    int slot[kUnroll];
+    uint32_t w[kUnroll];                                         // the row's bins of the four features
+    int2 qh[kUnroll];
+    // (global address space stated: plain pointers make flat loads, which also count as LDS
+    // traffic and would make every wait for them a wait for the atomics too)
+    auto g_node = FS_GLOBAL(const uint16_t, node_of);
+    auto g_words = FS_GLOBAL(const uint32_t, words);
+    auto g_qh = FS_GLOBAL(const int2, qh_of);
+    auto fetch = [&](int base, int (&sl)[kUnroll], uint32_t (&ww)[kUnroll], int2 (&q)[kUnroll]) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            if (base + u * kHistThreads >= row1 || (unsigned)slot[u] >= (unsigned)slots)
-                continue;
+            const uint32_t r = (uint32_t)min(base + u * kHistThreads, row1 - 1);   // 32-bit offsets from uniform bases
+            sl[u] = (int)g_node[r] - node0;
+            ww[u] = g_words[r];
+            q[u] = g_qh[r];
+        }
+    };
+    if (row0 < row1)
+        fetch(row0 + threadIdx.x, slot, w, qh);
+    for (int base = row0 + threadIdx.x; base < row1; base += kHistThreads * kUnroll) {
+        int n_slot[kUnroll];
+        uint32_t n_w[kUnroll];
+        int2 n_qh[kUnroll];
+        fetch(base + kHistThreads * kUnroll, n_slot, n_w, n_qh);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const bool counts = base + u * kHistThreads < row1 && (unsigned)slot[u] < (unsigned)slots;
             const unsigned long long both =
                 (unsigned long long)((long long)qh[u].x * ((long long)1 << hb) + (long long)qh[u].y);
+            const int row_at = slot[u] * (kHistFeats * kBins);
 #pragma unroll
-            for (int fi = 0; fi < 4; ++fi) {
+            for (int fi = 0; fi < kHistFeats; ++fi) {
                 const int b = (w[u] >> (8 * fi)) & 255;
-                if (fi >= nf || b == hot[fi])
-                    continue;                                    // rebuilt from the node's total
-                const int at = (slot[u] * 4 + fi) * kBins + b;
+                // (a feature past the family's last has hot = 256 and its bins are 0: harmless)
+                // (mask arithmetic, not a conditional: the compiler turns that into a branch)
+                const int take = -(int)(counts & (b != hot[fi]));
+                const int at = trash + ((row_at + b - trash) & take) + fi * kBins;
                 if (PACKED) {
                     atomicAdd(&lds_hist[at], both);
                 } else {
                     atomicAdd(&lds_hist[at], (unsigned long long)(long long)qh[u].x);
-                    atomicAdd(&lds_h[at], (unsigned long long)qh[u].y);
+                    atomicAdd(&lds_hist[at + (at >= trash ? 0 : pairs * kBins)], (unsigned long long)qh[u].y);
                 }
             }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            slot[u] = n_slot[u];
+            w[u] = n_w[u];
+            qh[u] = n_qh[u];
         }
     }
     __syncthreads();
@@ -499,7 +530,7 @@ __device__ __forceinline__ void hist_run(const TrainDesc &d, const Params &prm,
         // (one wavefront per (node, feature)); nothing goes through the global buffer.
         const int lane = threadIdx.x & 63;
         for (int pair = threadIdx.x >> 6; pair < pairs; pair += kHistThreads / 64) {
-            const int slot = pair >> 2, fi = pair & 3;
+            const int slot = pair / kHistFeats, fi = pair % kHistFeats;
             const int node = node0 + slot;
             if (fi >= nf || d.h_state[node] != kOpen)
                 continue;
@@ -507,13 +538,15 @@ __device__ __forceinline__ void hist_run(const TrainDesc &d, const Params &prm,
 #pragma unroll
             for (int k = 0; k < 4; ++k)
                 bin_at(pair * kBins + 4 * lane + k, g[k], h[k]);
+            // The pair's bins are in registers now and no other wavefront reads them: their LDS
+            // serves as the search's scratch (a wavefront's LDS accesses complete in order).
             wave_best_cut(d, prm, node, f0 + fi, (abs0 + slot) * d.n_features + f0 + fi, lane, g, h,
-                          cut_scratch + (threadIdx.x >> 6) * kCutScratchBytes);
+                          (unsigned char *)(lds_hist + pair * kBins));
         }
     } else {
         for (int i = threadIdx.x; i < pairs * kBins; i += kHistThreads) {
             const int pair = i / kBins, b = i - pair * kBins;
-            const int slot = pair >> 2, fi = pair & 3;
+            const int slot = pair / kHistFeats, fi = pair % kHistFeats;
             long long g, h;
             bin_at(i, g, h);
             if (fi >= nf || h == 0)
@@ -531,17 +564,15 @@ __global__ void __launch_bounds__(kHistThreads)
 train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, int rows_per_slab,
                   int n_slabs, int hb, int sorted, Params prm)
 {
-    extern __shared__ unsigned long long lds_raw[];              // cut-search scratch, then the histograms
-    unsigned char *cut_scratch = (unsigned char *)lds_raw;
-    unsigned long long *lds_hist = lds_raw + kHistCutScratch / 8;
+    extern __shared__ unsigned long long lds_hist[];
     const TrainDesc &d = descs[blockIdx.z / passes];
     const int pass = blockIdx.z % passes;
     int row0 = blockIdx.x * rows_per_slab;
-    const int f0 = blockIdx.y * 4;
+    const int f0 = blockIdx.y * kHistFeats;
     if (row0 >= d.n_rows || f0 >= d.n_features)
         return;
     int row1 = min(row0 + rows_per_slab, d.n_rows);
-    const int nf = min(4, d.n_features - f0);
+    const int nf = min(kHistFeats, d.n_features - f0);
     const int n_slots = 1 << level;
     const int slots = min(PACKED ? kHistSlotsPacked : kHistSlotsWide, n_slots);
     const int abs0 = pass * slots;                               // first node of the pass, within the level
@@ -552,9 +583,9 @@ train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, in
         row0 = d.seg_start[abs0 >> up];
         row1 = d.seg_start[((abs0 + slots - 1) >> up) + 1];
     }
-    int hot[4];
+    int hot[kHistFeats];
 #pragma unroll
-    for (int fi = 0; fi < 4; ++fi)
+    for (int fi = 0; fi < kHistFeats; ++fi)
         hot[fi] = fi < nf ? d.hot_bin[f0 + fi] : 256;           // 256: no bin, nothing is skipped
     const uint32_t *__restrict__ words =
         (const uint32_t *)(sorted ? d.s_bins : d.bins) + (int64_t)blockIdx.y * d.r_pad;
@@ -563,16 +594,16 @@ train_hist_kernel(const TrainDesc *__restrict__ descs, int level, int passes, in
     if (PACKED) {
         if (*d.abs_q < (1ull << (63 - hb))) {
             hist_run<true>(d, prm, lds_hist, node0, abs0, slots, row0, row1, f0, nf, hot, words, node_of, qh_of,
-                           n_slabs, hb, cut_scratch);
+                           n_slabs, hb);
         } else {
             const int half = slots > 1 ? slots / 2 : 1;          // the wide form takes twice the LDS per node
             for (int s = 0; s < slots; s += half)
                 hist_run<false>(d, prm, lds_hist, node0 + s, abs0 + s, half, row0, row1, f0, nf, hot, words,
-                                node_of, qh_of, n_slabs, 0, cut_scratch);
+                                node_of, qh_of, n_slabs, 0);
         }
     } else {
         hist_run<false>(d, prm, lds_hist, node0, abs0, slots, row0, row1, f0, nf, hot, words, node_of, qh_of,
-                        n_slabs, 0, cut_scratch);
+                        n_slabs, 0);
     }
 }
 
@@ -1348,10 +1379,10 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
         if (!hist_configured[dev]) {
             FS_HIP(hipFuncSetAttribute((const void *)train_hist_kernel<true>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kHistSlotsPacked * 4 * kBins * 8 + kHistCutScratch));
+                                       kHistSlotsPacked * kHistFeats * kBins * 8 + kHistTrashWords * 8));
             FS_HIP(hipFuncSetAttribute((const void *)train_hist_kernel<false>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kHistSlotsWide * 4 * kBins * 16 + kHistCutScratch));
+                                       kHistSlotsWide * kHistFeats * kBins * 16 + kHistTrashWords * 8));
             hist_configured[dev] = true;
         }
     }
@@ -1382,18 +1413,18 @@ extern "C" int fs_train_boost(int32_t n_trainers, fs_trainer *const *trainers, i
             const int per_pass = packed ? kHistSlotsPacked : kHistSlotsWide;
             const int slots = n_slots < per_pass ? n_slots : per_pass;
             const int passes = n_slots / slots;
-            const dim3 hgrid((unsigned)n_slabs, (unsigned)((max_feat + 3) / 4), nt * passes);
+            const dim3 hgrid((unsigned)n_slabs, (unsigned)((max_feat + kHistFeats - 1) / kHistFeats), nt * passes);
             prof_start(kKernTrainHist, stream);
             if (packed) {
-                // a lone node still needs the 16 KB of its wide form for the fall-back
-                size_t lds = (size_t)slots * 4 * kBins * 8;
-                if (lds < (size_t)4 * kBins * 16)
-                    lds = (size_t)4 * kBins * 16;
-                hipLaunchKernelGGL(train_hist_kernel<true>, hgrid, dim3(kHistThreads), lds + kHistCutScratch,
+                // a lone node still needs the 8 KB of its wide form for the fall-back
+                size_t lds = (size_t)slots * kHistFeats * kBins * 8;
+                if (lds < (size_t)kHistFeats * kBins * 16)
+                    lds = (size_t)kHistFeats * kBins * 16;
+                hipLaunchKernelGGL(train_hist_kernel<true>, hgrid, dim3(kHistThreads), lds + kHistTrashWords * 8,
                                    stream, d, level, passes, rows_per_slab, n_slabs, hb, sorted, prm);
             } else {
                 hipLaunchKernelGGL(train_hist_kernel<false>, hgrid, dim3(kHistThreads),
-                                   (size_t)slots * 4 * kBins * 16 + kHistCutScratch, stream, d, level, passes,
+                                   (size_t)slots * kHistFeats * kBins * 16 + kHistTrashWords * 8, stream, d, level, passes,
                                    rows_per_slab, n_slabs, 0, sorted, prm);
             }
             prof_stop(stream);
