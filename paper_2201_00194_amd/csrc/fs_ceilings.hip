@@ -180,7 +180,7 @@ static double run_lds(const char *name, Pattern pat, int waves, int lds_bytes, i
 // trees in the traversal kernel's node format (8 bytes: threshold, (feature*256)<<16 | left
 // child offset, right child next to left), features in a lane-per-bank tile.
 template <int K>
-__global__ void __launch_bounds__(768) visit_kernel(const uint32_t *__restrict__ image, int image_bytes, int n_trees,
+__global__ void __launch_bounds__(1024) visit_kernel(const uint32_t *__restrict__ image, int image_bytes, int n_trees,
                                                     int tree_bytes, int depth, int n_features, int rounds,
                                                     uint32_t *out)
 {
@@ -416,7 +416,7 @@ int main()
 
     printf("Synthetic lock-step visit loop (8-byte nodes, fp32 tile, two tiles, whole LDS)\n");
     double visit8 = 1e9, visit6 = 1e9;
-    for (int waves : {8, 12}) {
+    for (int waves : {8, 12, 16}) {
         double c = run_visits(waves, 8, n_cu, d_out);
         if (c < visit8) visit8 = c;
         c = run_visits(waves, 6, n_cu, d_out);
