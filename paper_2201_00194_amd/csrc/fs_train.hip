@@ -274,7 +274,55 @@ __device__ __forceinline__ double split_gain(long long GL, long long HL, long lo
     return (t1 + t2) - t3;
 }
 
-__device__ __forceinline__ long long shfl_up_ll(long long v, int off) { return __shfl_up(v, off); }
+// Cross-lane steps of the cut search as DPP moves (register to register, no trip through the
+// LDS crossbar as with __shfl): CTRL 0x110 + n = the lane n places down in its row of 16,
+// 0x142 / 0x143 = last lane of the previous row / of the first two rows, for the rows named in
+// ROW_MASK.  A lane without a source gets 0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_i(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ long long dpp_ll(long long v)
+{
+    const int lo = dpp_i<CTRL, ROW_MASK>((int)v), hi = dpp_i<CTRL, ROW_MASK>((int)(v >> 32));
+    return (long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned long long)(unsigned)lo);
+}
+
+// Inclusive prefix sum over the 64 lanes: four doubling steps inside the rows of 16, then the
+// total of row 0 (2) goes to row 1 (3), then the total of the first 32 lanes to the last 32.
+__device__ __forceinline__ long long wave_prefix_ll(long long v)
+{
+    v += dpp_ll<0x111, 0xf>(v);
+    v += dpp_ll<0x112, 0xf>(v);
+    v += dpp_ll<0x114, 0xf>(v);
+    v += dpp_ll<0x118, 0xf>(v);
+    v += dpp_ll<0x142, 0xa>(v);
+    v += dpp_ll<0x143, 0xc>(v);
+    return v;
+}
+
+__device__ __forceinline__ long long lane63_ll(long long v)
+{
+    const int lo = __builtin_amdgcn_readlane((int)v, 63), hi = __builtin_amdgcn_readlane((int)(v >> 32), 63);
+    return (long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned long long)(unsigned)lo);
+}
+
+// One step of the arg-max over the lanes (largest gain, lowest cut on ties; cut 0 = nothing):
+// the lane takes the other lane's pair if that is better.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void best_step(double &best, int &best_cut)
+{
+    const long long bits = __double_as_longlong(best);
+    const double og = __longlong_as_double(dpp_ll<CTRL, ROW_MASK>(bits));
+    const int oc = dpp_i<CTRL, ROW_MASK>(best_cut);
+    if (oc != 0 && (best_cut == 0 || og > best || (og == best && oc < best_cut))) {
+        best = og;
+        best_cut = oc;
+    }
+}
 
 // Best cut of feature f for the open node `node`, by one wavefront: lane l holds bins 4l..4l+3
 // (g, h; the feature's most frequent bin holds 0 and is rebuilt here from the node's totals)
@@ -297,17 +345,10 @@ __device__ __forceinline__ void wave_best_cut(const TrainDesc &d, const Params &
     const long long G = d.h_G[node], H = d.h_H[node];
     const int hot = d.hot_bin[f];
     // inclusive prefix sums over the 256 bins, the hot bin still at 0
-    long long pg = g[0] + g[1] + g[2] + g[3], ph = h[0] + h[1] + h[2] + h[3];   // this lane's total -> scan
-    const long long lane_g = pg, lane_h = ph;
-    for (int off = 1; off < 64; off <<= 1) {
-        const long long ug = shfl_up_ll(pg, off), uh = shfl_up_ll(ph, off);
-        if (lane >= off) {
-            pg += ug;
-            ph += uh;
-        }
-    }
+    const long long lane_g = g[0] + g[1] + g[2] + g[3], lane_h = h[0] + h[1] + h[2] + h[3];
+    const long long pg = wave_prefix_ll(lane_g), ph = wave_prefix_ll(lane_h);
     // what the counted bins lack of the node's totals sits in the hot bin
-    const long long hot_g = G - __shfl(pg, 63), hot_h = H - __shfl(ph, 63);
+    const long long hot_g = G - lane63_ll(pg), hot_h = H - lane63_ll(ph);
     long long before_g = pg - lane_g, before_h = ph - lane_h;
     if ((hot >> 2) < lane) {
         before_g += hot_g;
@@ -394,14 +435,15 @@ __device__ __forceinline__ void wave_best_cut(const TrainDesc &d, const Params &
     }
     double best = gain;
     int best_cut = cut;
-    for (int off = 32; off > 0; off >>= 1) {                     // largest gain, lowest cut on ties
-        const double og2 = __shfl_xor(best, off);
-        const int oc = __shfl_xor(best_cut, off);
-        if (oc != 0 && (best_cut == 0 || og2 > best || (og2 == best && oc < best_cut))) {
-            best = og2;
-            best_cut = oc;
-        }
-    }
+    // largest gain, lowest cut on ties: the same steps as the prefix sum leave the best of all
+    // lanes in lane 63
+    best_step<0x111, 0xf>(best, best_cut);
+    best_step<0x112, 0xf>(best, best_cut);
+    best_step<0x114, 0xf>(best, best_cut);
+    best_step<0x118, 0xf>(best, best_cut);
+    best_step<0x142, 0xa>(best, best_cut);
+    best_step<0x143, 0xc>(best, best_cut);
+    best_cut = __builtin_amdgcn_readlane(best_cut, 63);
     if (best_cut == 0) {
         if (lane == 0) {
             d.best_gain[pair] = 0.0;
