@@ -39,6 +39,32 @@ def test_library_exports_every_declared_symbol():
     assert lib.fs_last_error() is not None
 
 
+def test_tuning_options_of_header_binding_and_library_agree():
+    """The FS_TUNE_* options are numbered once, in familyseer.h; the Python binding repeats the
+    numbers and the library accepts exactly that many (no GPU needed: fs_tune_set only stores)."""
+    src = re.sub(r"/\*.*?\*/", "", open(HEADERS[0]).read(), flags=re.S)
+    enum = dict((k, int(v)) for k, v in re.findall(r"\b(FS_TUNE_[A-Z_]+)\s*=\s*(\d+)", src))
+    n = enum.pop("FS_TUNE_OPTIONS")
+    assert sorted(enum.values()) == list(range(n))
+    api_src = open(os.path.join(ROOT, "paper_2201_00194_amd", "api.py")).read()
+    m = re.search(r"\(((?:\s*FS_TUNE_[A-Z_]+,?)+)\)\s*=\s*range\((\d+)\)", api_src)
+    assert m, "api.py no longer lists the options as one range"
+    names = re.findall(r"FS_TUNE_[A-Z_]+", m.group(1))
+    assert int(m.group(2)) == n and names == sorted(enum, key=enum.get)
+    if not os.path.exists(LIB):
+        from paper_2201_00194_amd import build
+        build.build()
+    lib = ctypes.CDLL(LIB)
+    lib.fs_tune_set.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    lib.fs_tune_get.argtypes = [ctypes.c_int32]
+    lib.fs_tune_get.restype = ctypes.c_int32
+    for opt in range(n):
+        assert lib.fs_tune_get(opt) == -1                 # automatic choice
+        assert lib.fs_tune_set(opt, 3) == 0 and lib.fs_tune_get(opt) == 3
+        assert lib.fs_tune_set(opt, -1) == 0 and lib.fs_tune_get(opt) == -1
+    assert lib.fs_tune_set(n, 1) != 0 and lib.fs_tune_set(-1, 1) != 0
+
+
 def test_host_side_validation_needs_no_gpu():
     """Argument errors are found on the host before any device work."""
     if not os.path.exists(LIB):
