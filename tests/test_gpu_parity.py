@@ -430,6 +430,16 @@ def test_workgroups_that_take_several_tile_groups(api, oracle, tune, groups):
     devs = run_families(api, case.families, api.FS_COLBLOCK64, want_leaves=False)
     for f, d in zip(case.families, devs):
         check_family(oracle, f, d, check_leaves=False)
+    # both layouts in one call: the workgroups of the row-major families take one group each,
+    # the others several, and the workgroup counts of the launch have to add up
+    import torch
+    devs = [api.DeviceFamily(f, layout=i % 2, want_row_score=True, want_leaf_idx=i % 3 == 0)
+            for i, f in enumerate(fams)]
+    api.fs_score_families([d.family() for d in devs])
+    api.fs_topk([d.topk_request() for d in devs])
+    torch.cuda.synchronize()
+    for f, d in zip(fams, devs):
+        check_family(oracle, f, d)
 
 
 def test_models_outside_the_lds_formats_take_the_global_kernel(api, oracle):
