@@ -411,6 +411,8 @@ int main()
             run_lds<4, 8>("b32, random within 256 B (64 4-byte nodes)", kRandomSmall, waves, 65536, 256, n_cu, d_out);
             run_lds<4, 8>("b32, random within 1 KB (256 4-byte nodes)", kRandomSmall, waves, 65536, 1024, n_cu, d_out);
             run_lds<4, 8>("b32, random within 4 KB (1024 4-byte nodes)", kRandomSmall, waves, 65536, 4096, n_cu, d_out);
+            run_lds<16, 8>("b128, random within 1 KB (64 16-byte nodes)", kRandomSmall, waves, 65536, 1024, n_cu, d_out);
+            run_lds<16, 8>("b128, random within 4 KB (256 16-byte nodes)", kRandomSmall, waves, 65536, 4096, n_cu, d_out);
         }
     }
 
