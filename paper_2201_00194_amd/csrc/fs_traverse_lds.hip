@@ -164,248 +164,251 @@ traverse_lds_kernel(const FamDesc *__restrict__ descs, int n_families, int mode,
     const int per_tile = F * 16;                           // 16-byte pieces per tile
     u32x4 pf[kPrefetchRegs];
     ChunkView h = load_chunk(d.chunks);
-  {
-    // the workgroup's first group: chunk and tiles straight from memory
-    const int tile_first = g_first * T;
-    const int tiles_here = min(T, n_tiles - tile_first);
-
-    // ---- first chunk: global -> registers (lands while the tiles are being fetched) ----
-    // Loads are unconditional with clamped indices (no branches between them, so they all go
-    // out back to back); only the LDS writes are predicated.
-    // (Row-major input stages its rows at LDS offset 0 first, so there the chunk waits in
-    // registers; column-blocked input lets chunk and tiles go straight from memory to LDS.)
-    const bool direct = d.layout != FS_ROWMAJOR;
     {
-        auto src = FS_GLOBAL(const u32x4, d.image + h.byte_off);
-        const int n16 = (int)(h.bytes >> 4);
-        if (direct) {
-            const int done = lds_fill_direct(src, 0u, n16, wave, kLdsWaves, lane);
-            if (done + tid < n16)
-                pf[0] = src[done + tid];                   // fewer than 64 pieces are left
-        } else {
+        // the workgroup's first group: chunk and tiles straight from memory
+        const int tile_first = g_first * T;
+        const int tiles_here = min(T, n_tiles - tile_first);
+
+        // ---- first chunk: global -> registers (lands while the tiles are being fetched) ----
+        // Loads are unconditional with clamped indices (no branches between them, so they all go
+        // out back to back); only the LDS writes are predicated.
+        // (Row-major input stages its rows at LDS offset 0 first, so there the chunk waits in
+        // registers; column-blocked input lets chunk and tiles go straight from memory to LDS.)
+        const bool direct = d.layout != FS_ROWMAJOR;
+        {
+            auto src = FS_GLOBAL(const u32x4, d.image + h.byte_off);
+            const int n16 = (int)(h.bytes >> 4);
+            if (direct) {
+                const int done = lds_fill_direct(src, 0u, n16, wave, kLdsWaves, lane);
+                if (done + tid < n16)
+                    pf[0] = src[done + tid];                   // fewer than 64 pieces are left
+            } else {
 #pragma unroll
-            for (int j = 0; j < kPrefetchRegs; ++j)
-                pf[j] = src[min(tid + j * kLdsThreads, n16 - 1)];
+                for (int j = 0; j < kPrefetchRegs; ++j)
+                    pf[j] = src[min(tid + j * kLdsThreads, n16 - 1)];
+            }
         }
-    }
-    // ---- feature tiles ----
-    if (d.layout == FS_ROWMAJOR) {
-        // Row-major input (the host side only sends it here when F % 4 == 0 and at least 8
-        // padded rows fit below tile0): a tile is 64 consecutive rows = one contiguous run.  It
-        // is fetched with 16-byte loads into a staging area at LDS offset 0 (the chunk region,
-        // not yet in use) with a row stride of F + 1 words, as many rows at a time as fit, then
-        // copied across with lane = row: the odd stride makes the column reads conflict-free,
-        // the writes are whole columns.
-        const uint32_t Fp = (uint32_t)F + 1u;
-        const int stage_rows = min(64, (int)(tile0 / (4u * Fp)));   // rows the staging area takes
-        for (int t = 0; t < tiles_here; ++t) {
-            const int r0 = (tile_first + t) * 64;
-            const int rows_here = min(64, d.n_rows - r0);
-            for (int s0 = 0; s0 < 64; s0 += stage_rows) {            // uniform trip count
-                const int s1 = min(s0 + stage_rows, rows_here);      // rows [s0, s1) of the tile
-                if (s0 < s1) {
-                    auto src = FS_GLOBAL(const u32x4, d.features + (int64_t)(r0 + s0) * F);
-                    const int n16 = (s1 - s0) * (F >> 2);
-                    for (int base = tid; base < n16; base += kTileBatch * kLdsThreads) {
-                        u32x4 t4[kTileBatch];
+        // ---- feature tiles ----
+        if (d.layout == FS_ROWMAJOR) {
+            // Row-major input (the host side only sends it here when F % 4 == 0 and at least 8
+            // padded rows fit below tile0): a tile is 64 consecutive rows = one contiguous run.  It
+            // is fetched with 16-byte loads into a staging area at LDS offset 0 (the chunk region,
+            // not yet in use) with a row stride of F + 1 words, as many rows at a time as fit, then
+            // copied across with lane = row: the odd stride makes the column reads conflict-free,
+            // the writes are whole columns.
+            const uint32_t Fp = (uint32_t)F + 1u;
+            const int stage_rows = min(64, (int)(tile0 / (4u * Fp)));   // rows the staging area takes
+            for (int t = 0; t < tiles_here; ++t) {
+                const int r0 = (tile_first + t) * 64;
+                const int rows_here = min(64, d.n_rows - r0);
+                for (int s0 = 0; s0 < 64; s0 += stage_rows) {            // uniform trip count
+                    const int s1 = min(s0 + stage_rows, rows_here);      // rows [s0, s1) of the tile
+                    if (s0 < s1) {
+                        auto src = FS_GLOBAL(const u32x4, d.features + (int64_t)(r0 + s0) * F);
+                        const int n16 = (s1 - s0) * (F >> 2);
+                        for (int base = tid; base < n16; base += kTileBatch * kLdsThreads) {
+                            u32x4 t4[kTileBatch];
 #pragma unroll
-                        for (int q = 0; q < kTileBatch; ++q)
-                            t4[q] = src[min(base + q * kLdsThreads, n16 - 1)];
+                            for (int q = 0; q < kTileBatch; ++q)
+                                t4[q] = src[min(base + q * kLdsThreads, n16 - 1)];
 #pragma unroll
-                        for (int q = 0; q < kTileBatch; ++q) {
-                            const int i = base + q * kLdsThreads;
-                            if (i < n16) {
-                                const int e = 4 * i, row = e / F, col = e - row * F;
-                                const uint32_t at = 4u * ((uint32_t)row * Fp + (uint32_t)col);
-                                lds_store_f(at, __uint_as_float(t4[q].x));
-                                lds_store_f(at + 4u, __uint_as_float(t4[q].y));
-                                lds_store_f(at + 8u, __uint_as_float(t4[q].z));
-                                lds_store_f(at + 12u, __uint_as_float(t4[q].w));
+                            for (int q = 0; q < kTileBatch; ++q) {
+                                const int i = base + q * kLdsThreads;
+                                if (i < n16) {
+                                    const int e = 4 * i, row = e / F, col = e - row * F;
+                                    const uint32_t at = 4u * ((uint32_t)row * Fp + (uint32_t)col);
+                                    lds_store_f(at, __uint_as_float(t4[q].x));
+                                    lds_store_f(at + 4u, __uint_as_float(t4[q].y));
+                                    lds_store_f(at + 8u, __uint_as_float(t4[q].z));
+                                    lds_store_f(at + 12u, __uint_as_float(t4[q].w));
+                                }
                             }
+                        }
+                    }
+                    __syncthreads();
+                    if (lane >= s0 && lane < s0 + stage_rows) {
+                        for (int j = wave; j < F; j += kLdsWaves) {
+                            const uint32_t from = 4u * ((uint32_t)(lane - s0) * Fp + (uint32_t)j);
+                            const uint32_t to =
+                                tile0 + (uint32_t)t * tile_bytes + (uint32_t)j * 256u + 4u * (uint32_t)lane;
+                            lds_store_f(to, lane < s1 ? lds_f(from) : 0.0f);
+                        }
+                    }
+                    __syncthreads();   // the staging area is free again (next rows, then the chunk)
+                }
+            }
+            if (tid < 64 * tiles_here)
+                lds_store_f(tile0 + (uint32_t)(tid >> 6) * tile_bytes + (uint32_t)F * 256u +
+                                4u * (uint32_t)(tid & 63), __builtin_nanf(""));
+        } else {
+            // consecutive tiles are one contiguous run in HBM
+            auto src = FS_GLOBAL(const u32x4, d.features + (int64_t)tile_first * F * 64);
+            const int n16 = tiles_here * per_tile;
+            if ((per_tile & 63) == 0) {
+                // F % 4 == 0: every group of 64 pieces lies inside one tile
+                const int n_groups = n16 >> 6;
+                for (int g = wave; g < n_groups; g += kLdsWaves) {
+                    const int i0 = g << 6;
+                    const int t = i0 / per_tile, j0 = i0 - t * per_tile;
+                    lds_fill_direct(src + i0, tile0 + (uint32_t)t * tile_bytes + 16u * (uint32_t)j0, 64, 0, 1,
+                                    lane);
+                }
+            } else
+            // two tiles are 7 pieces per thread: one batch, one exposure of the HBM latency
+            for (int base = tid; base < n16; base += kTileBatch * kLdsThreads) {
+                u32x4 t4[kTileBatch];
+#pragma unroll
+                for (int q = 0; q < kTileBatch; ++q)
+                    t4[q] = src[min(base + q * kLdsThreads, n16 - 1)];
+#pragma unroll
+                for (int q = 0; q < kTileBatch; ++q) {
+                    const int i = base + q * kLdsThreads;
+                    if (i < n16) {
+                        const int t = i / per_tile, j = i - t * per_tile;
+                        lds_store_u4(tile0 + (uint32_t)t * tile_bytes + 16u * (uint32_t)j, t4[q]);
+                    }
+                }
+            }
+            if (tid < 64 * tiles_here)
+                lds_store_f(tile0 + (uint32_t)(tid >> 6) * tile_bytes + (uint32_t)F * 256u +
+                                4u * (uint32_t)(tid & 63), __builtin_nanf(""));
+        }
+        {
+            const int n16 = (int)(h.bytes >> 4);
+            if (direct) {
+                const int i = (n16 & ~63) + tid;
+                if (i < n16)
+                    lds_store_u4(16u * (uint32_t)i, pf[0]);
+                lds_direct_wait();
+            } else {
+#pragma unroll
+                for (int j = 0; j < kPrefetchRegs; ++j) {
+                    const int i = tid + j * kLdsThreads;
+                    if (i < n16)
+                        lds_store_u4(16u * (uint32_t)i, pf[j]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+  // Later groups of the workgroup arrive through registers (tp and pf below).
+    for (int grp = g_first; grp < g_end; ++grp) {
+        const int tile_first = grp * T;
+        const int tiles_here = min(T, n_tiles - tile_first);
+        const bool active = my_tile < tiles_here;
+        const int r = (tile_first + my_tile) * 64 + lane;
+        float acc = d.bias;
+        uint16_t *leaf_row = nullptr;
+        if (DUMP) {
+            if (active && d.leaf_idx && r < d.n_rows)
+                leaf_row = d.leaf_idx + (int64_t)r * d.n_trees;
+        }
+        const bool compact = d.compact != 0;
+        const int n_chunks = d.n_chunks;
+        const uint32_t val_stride = (uint32_t)T * 256u;        // bytes between trees' value rows
+
+        // Wavefronts 0..T-1 do the ordered sums.  When the others can carry a whole chunk in their
+        // prefetch registers they copy it alone, so a sum and the copy run side by side.
+        const int n_copiers = kLdsThreads - 64 * T;
+        for (int c = 0; c < n_chunks; ++c) {
+            // After the last chunk of a group that is not the workgroup's last, the next group's
+            // tiles travel the same way as the next chunk (and the first chunk comes back when the
+            // model has more than one).
+            const bool last = c + 1 == n_chunks;
+            const bool wrap = MULTI && last && grp + 1 < g_end;
+            const bool fetch = !last || (wrap && n_chunks > 1);
+            ChunkView hn = h;
+            int n16_next = 0, cp_id = tid, cp_n = kLdsThreads;
+            u32x4 tp[kLdsTileRegs];
+            if (fetch) {                                       // next chunk: global -> registers
+                hn = load_chunk(d.chunks + (last ? 0 : c + 1));
+                auto src = FS_GLOBAL(const u32x4, d.image + hn.byte_off);
+                n16_next = (int)(hn.bytes >> 4);
+                if (n16_next <= kPrefetchRegs * n_copiers) {
+                    cp_n = n_copiers;
+                    cp_id = tid - 64 * T;                      // negative in the summing wavefronts
+                }
+                if (cp_id >= 0) {
+#pragma unroll
+                    for (int j = 0; j < kPrefetchRegs; ++j)
+                        pf[j] = src[min(cp_id + j * cp_n, n16_next - 1)];
+                }
+            }
+            if (wrap) {
+                const int next_first = (grp + 1) * T;
+                const int n16t = min(T, n_tiles - next_first) * per_tile;
+                auto src = FS_GLOBAL(const u32x4, d.features + (int64_t)next_first * F * 64);
+#pragma unroll
+                for (int q = 0; q < kLdsTileRegs; ++q)
+                    tp[q] = src[min(tid + q * kLdsThreads, n16t - 1)];
+            }
+            const int n = uniform((int)h.n_trees);
+            const uint32_t val0 = tile0 - (uint32_t)n * val_stride;   // packing keeps it above the image
+            if (active) {
+                const uint32_t val_addr = val0 + (uint32_t)my_tile * 256u + 4u * (uint32_t)lane;
+                const uint16_t *ids = d.slot_ids + h.slot_off;
+                uint16_t *leaf_out = leaf_row ? leaf_row + h.first_tree : nullptr;
+                // this wavefront's runs of the chunk: record my_slot, then the records chained to it
+                uint32_t rec = (uint32_t)(kRunBytes * my_slot);
+                for (;;) {
+                    uint32_t tab[8];
+                    const uint32_t head = lds_u(rec);            // same address in every lane: broadcast
+#pragma unroll
+                    for (int k = 0; k < 8; ++k)
+                        tab[k] = lds_u(rec + 4u + 4u * (uint32_t)k);
+                    const uint32_t run = (uint32_t)uniform((int)head);
+                    const int count = (int)(run & 0xFu), depth = (int)(run >> 16);
+                    if (count == 0)
+                        break;                                   // idle slot
+                    if (compact)
+                        walk_n<true, DUMP>(count, tab, depth, lane_base, val_addr, val_stride, ids, leaf_out);
+                    else
+                        walk_n<false, DUMP>(count, tab, depth, lane_base, val_addr, val_stride, ids, leaf_out);
+                    const uint32_t next = (run >> 4) & 0xFFFu;
+                    if (next == 0)
+                        break;
+                    rec = (uint32_t)kRunBytes * (next - 1u);
+                }
+            }
+            __syncthreads();       // every walk of this chunk is done and its values are parked
+            if (active && my_slot == 0) {
+                const uint32_t va = val0 + (uint32_t)my_tile * 256u + 4u * (uint32_t)lane;
+                ordered_add_n(acc, va, val_stride, n);
+            }
+            if (fetch || wrap) {
+                // The next image may be long enough to reach into the value rows that are being
+                // summed right now (only when chunk sizes differ a lot): then wait for the readers.
+                if (fetch && 16u * (uint32_t)n16_next > val0)
+                    __syncthreads();
+                if (fetch && cp_id >= 0) {
+#pragma unroll
+                    for (int j = 0; j < kPrefetchRegs; ++j) {
+                        const int i = cp_id + j * cp_n;
+                        if (i < n16_next)
+                            lds_store_u4(16u * (uint32_t)i, pf[j]);
+                    }
+                }
+                if (wrap) {                                    // every walk of this group is done
+                    const int n16t = min(T, n_tiles - (grp + 1) * T) * per_tile;
+#pragma unroll
+                    for (int q = 0; q < kLdsTileRegs; ++q) {
+                        const int i = tid + q * kLdsThreads;
+                        if (i < n16t) {
+                            // piece i of tile t sits 16 * i + 256 * t above tile0 (the NaN column of
+                            // every tile before it); at most kLdsMaxTiles = 3 tiles, so no division
+                            const int t = (i >= per_tile ? 1 : 0) + (i >= 2 * per_tile ? 1 : 0);
+                            lds_store_u4(tile0 + 16u * (uint32_t)i + 256u * (uint32_t)t, tp[q]);
                         }
                     }
                 }
                 __syncthreads();
-                if (lane >= s0 && lane < s0 + stage_rows) {
-                    for (int j = wave; j < F; j += kLdsWaves) {
-                        const float v = lane < s1 ? lds_f(4u * ((uint32_t)(lane - s0) * Fp + (uint32_t)j)) : 0.0f;
-                        lds_store_f(tile0 + (uint32_t)t * tile_bytes + (uint32_t)j * 256u + 4u * (uint32_t)lane, v);
-                    }
-                }
-                __syncthreads();   // the staging area is free again (next rows, then the chunk)
             }
+            h = hn;
         }
-        if (tid < 64 * tiles_here)
-            lds_store_f(tile0 + (uint32_t)(tid >> 6) * tile_bytes + (uint32_t)F * 256u +
-                            4u * (uint32_t)(tid & 63), __builtin_nanf(""));
-    } else {
-        // consecutive tiles are one contiguous run in HBM
-        auto src = FS_GLOBAL(const u32x4, d.features + (int64_t)tile_first * F * 64);
-        const int n16 = tiles_here * per_tile;
-        if ((per_tile & 63) == 0) {
-            // F % 4 == 0: every group of 64 pieces lies inside one tile
-            const int n_groups = n16 >> 6;
-            for (int g = wave; g < n_groups; g += kLdsWaves) {
-                const int i0 = g << 6;
-                const int t = i0 / per_tile, j0 = i0 - t * per_tile;
-                lds_fill_direct(src + i0, tile0 + (uint32_t)t * tile_bytes + 16u * (uint32_t)j0, 64, 0, 1, lane);
-            }
-        } else
-        // two tiles are 7 pieces per thread: one batch, one exposure of the HBM latency
-        for (int base = tid; base < n16; base += kTileBatch * kLdsThreads) {
-            u32x4 t4[kTileBatch];
-#pragma unroll
-            for (int q = 0; q < kTileBatch; ++q)
-                t4[q] = src[min(base + q * kLdsThreads, n16 - 1)];
-#pragma unroll
-            for (int q = 0; q < kTileBatch; ++q) {
-                const int i = base + q * kLdsThreads;
-                if (i < n16) {
-                    const int t = i / per_tile, j = i - t * per_tile;
-                    lds_store_u4(tile0 + (uint32_t)t * tile_bytes + 16u * (uint32_t)j, t4[q]);
-                }
-            }
-        }
-        if (tid < 64 * tiles_here)
-            lds_store_f(tile0 + (uint32_t)(tid >> 6) * tile_bytes + (uint32_t)F * 256u +
-                            4u * (uint32_t)(tid & 63), __builtin_nanf(""));
-    }
-    {
-        const int n16 = (int)(h.bytes >> 4);
-        if (direct) {
-            const int i = (n16 & ~63) + tid;
-            if (i < n16)
-                lds_store_u4(16u * (uint32_t)i, pf[0]);
-            lds_direct_wait();
-        } else {
-#pragma unroll
-            for (int j = 0; j < kPrefetchRegs; ++j) {
-                const int i = tid + j * kLdsThreads;
-                if (i < n16)
-                    lds_store_u4(16u * (uint32_t)i, pf[j]);
-            }
-        }
-    }
-    __syncthreads();
-  }
-
-  // Later groups of the workgroup arrive through registers (tp and pf below).
-  for (int grp = g_first; grp < g_end; ++grp) {
-    const int tile_first = grp * T;
-    const int tiles_here = min(T, n_tiles - tile_first);
-    const bool active = my_tile < tiles_here;
-    const int r = (tile_first + my_tile) * 64 + lane;
-    float acc = d.bias;
-    uint16_t *leaf_row = nullptr;
-    if (DUMP) {
-        if (active && d.leaf_idx && r < d.n_rows)
-            leaf_row = d.leaf_idx + (int64_t)r * d.n_trees;
-    }
-    const bool compact = d.compact != 0;
-    const int n_chunks = d.n_chunks;
-    const uint32_t val_stride = (uint32_t)T * 256u;        // bytes between trees' value rows
-
-    // Wavefronts 0..T-1 do the ordered sums.  When the others can carry a whole chunk in their
-    // prefetch registers they copy it alone, so a sum and the copy run side by side.
-    const int n_copiers = kLdsThreads - 64 * T;
-    for (int c = 0; c < n_chunks; ++c) {
-        // After the last chunk of a group that is not the workgroup's last, the next group's
-        // tiles travel the same way as the next chunk (and the first chunk comes back when the
-        // model has more than one).
-        const bool last = c + 1 == n_chunks;
-        const bool wrap = MULTI && last && grp + 1 < g_end;
-        const bool fetch = !last || (wrap && n_chunks > 1);
-        ChunkView hn = h;
-        int n16_next = 0, cp_id = tid, cp_n = kLdsThreads;
-        u32x4 tp[kLdsTileRegs];
-        if (fetch) {                                       // next chunk: global -> registers
-            hn = load_chunk(d.chunks + (last ? 0 : c + 1));
-            auto src = FS_GLOBAL(const u32x4, d.image + hn.byte_off);
-            n16_next = (int)(hn.bytes >> 4);
-            if (n16_next <= kPrefetchRegs * n_copiers) {
-                cp_n = n_copiers;
-                cp_id = tid - 64 * T;                      // negative in the summing wavefronts
-            }
-            if (cp_id >= 0) {
-#pragma unroll
-                for (int j = 0; j < kPrefetchRegs; ++j)
-                    pf[j] = src[min(cp_id + j * cp_n, n16_next - 1)];
-            }
-        }
-        if (wrap) {
-            const int next_first = (grp + 1) * T;
-            const int n16t = min(T, n_tiles - next_first) * per_tile;
-            auto src = FS_GLOBAL(const u32x4, d.features + (int64_t)next_first * F * 64);
-#pragma unroll
-            for (int q = 0; q < kLdsTileRegs; ++q)
-                tp[q] = src[min(tid + q * kLdsThreads, n16t - 1)];
-        }
-        const int n = uniform((int)h.n_trees);
-        const uint32_t val0 = tile0 - (uint32_t)n * val_stride;   // packing keeps it above the image
-        if (active) {
-            const uint32_t val_addr = val0 + (uint32_t)my_tile * 256u + 4u * (uint32_t)lane;
-            const uint16_t *ids = d.slot_ids + h.slot_off;
-            uint16_t *leaf_out = leaf_row ? leaf_row + h.first_tree : nullptr;
-            // this wavefront's runs of the chunk: record my_slot, then the records chained to it
-            uint32_t rec = (uint32_t)(kRunBytes * my_slot);
-            for (;;) {
-                uint32_t tab[8];
-                const uint32_t head = lds_u(rec);            // same address in every lane: broadcast
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    tab[k] = lds_u(rec + 4u + 4u * (uint32_t)k);
-                const uint32_t run = (uint32_t)uniform((int)head);
-                const int count = (int)(run & 0xFu), depth = (int)(run >> 16);
-                if (count == 0)
-                    break;                                   // idle slot
-                if (compact)
-                    walk_n<true, DUMP>(count, tab, depth, lane_base, val_addr, val_stride, ids, leaf_out);
-                else
-                    walk_n<false, DUMP>(count, tab, depth, lane_base, val_addr, val_stride, ids, leaf_out);
-                const uint32_t next = (run >> 4) & 0xFFFu;
-                if (next == 0)
-                    break;
-                rec = (uint32_t)kRunBytes * (next - 1u);
-            }
-        }
-        __syncthreads();       // every walk of this chunk is done and its values are parked
-        if (active && my_slot == 0) {
-            const uint32_t va = val0 + (uint32_t)my_tile * 256u + 4u * (uint32_t)lane;
-            ordered_add_n(acc, va, val_stride, n);
-        }
-        if (fetch || wrap) {
-            // The next image may be long enough to reach into the value rows that are being
-            // summed right now (only when chunk sizes differ a lot): then wait for the readers.
-            if (fetch && 16u * (uint32_t)n16_next > val0)
-                __syncthreads();
-            if (fetch && cp_id >= 0) {
-#pragma unroll
-                for (int j = 0; j < kPrefetchRegs; ++j) {
-                    const int i = cp_id + j * cp_n;
-                    if (i < n16_next)
-                        lds_store_u4(16u * (uint32_t)i, pf[j]);
-                }
-            }
-            if (wrap) {                                    // every walk of this group is done
-                const int n16t = min(T, n_tiles - (grp + 1) * T) * per_tile;
-#pragma unroll
-                for (int q = 0; q < kLdsTileRegs; ++q) {
-                    const int i = tid + q * kLdsThreads;
-                    if (i < n16t) {
-                        // piece i of tile t sits 16 * i + 256 * t above tile0 (the NaN column of
-                        // every tile before it); at most kLdsMaxTiles = 3 tiles, so no division
-                        const int t = (i >= per_tile ? 1 : 0) + (i >= 2 * per_tile ? 1 : 0);
-                        lds_store_u4(tile0 + 16u * (uint32_t)i + 256u * (uint32_t)t, tp[q]);
-                    }
-                }
-            }
-            __syncthreads();
-        }
-        h = hn;
-    }
-    if (active && my_slot == 0 && r < d.n_rows)
-        FS_GLOBAL(float, d.row_score)[r] = acc;
-  }   // tile groups of this workgroup
+        if (active && my_slot == 0 && r < d.n_rows)
+            FS_GLOBAL(float, d.row_score)[r] = acc;
+    }   // tile groups of this workgroup
 }
 
 int launch_traverse_lds(const FamDesc *d_desc, int n_families, int mode, int total_blocks,
