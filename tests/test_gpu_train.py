@@ -99,6 +99,15 @@ def test_families_spanning_several_row_slabs(api, T, tune):
     check(api, T, ts, rounds=2, max_depth=6, eta=0.5, lam=1.0)
 
 
+def test_family_larger_than_one_slab_at_its_natural_size(api, T):
+    """The same path with nothing forced: a family of more than 65536 rows spans two slabs of its
+    own accord (two workgroups per feature group add into the global histograms, the split
+    kernel searches there)."""
+    ts = W.make_train_set(29, 12_000, stmts=(4, 9), n_features=12, max_cuts=63)
+    assert 65_536 < ts.n_rows < 131_072
+    check(api, T, ts, rounds=2, max_depth=4, eta=0.3, lam=1.0)
+
+
 def test_batched_families_train_independently(api, T):
     import torch
     sets = [W.make_train_set(30 + i, n, stmts=(1, 8), n_features=nf, max_cuts=mc)
