@@ -59,8 +59,10 @@ typedef struct fs_train_params {
  * may be asked for later (they size the buffers).  n_rows >= 1, n_programs >= 1.
  * The content of prog_off (DEVICE) is not validated: it must start at 0, be non-decreasing
  * and end at n_rows, as for fs_score_families; a malformed array gives undefined results.
- * The cut lists (HOST) are validated.  The binning work is enqueued on `stream`; the small
- * host arrays are copied with plain (synchronising) copies.
+ * The cut lists (HOST) are validated.  The call BLOCKS until its work on `stream` is done: the
+ * binning kernels run there, then the length of the longest program is read back (it sizes
+ * the curvature sums of the histograms); the small host arrays are copied with plain
+ * (synchronising) copies.  Create trainers outside latency-critical sections.
  * Errors: FS_EINVAL, FS_EUNSUPPORTED (limits), FS_ENOMEM, FS_EDEVICE.
  */
 int fs_trainer_create(fs_trainer **out, int32_t n_features, const float *features /* DEVICE */,
