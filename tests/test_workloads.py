@@ -101,3 +101,15 @@ def test_foresee_case_shape_and_shared_models():
         assert f.features.shape == (f.n_rows, 164) and f.model.n_trees == 5
     again = W.make_foresee_case(seed=3, scale=0.05, trees=5)
     assert all(np.array_equal(a.features, b.features) for a, b in zip(case.families, again.families))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before touching a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
