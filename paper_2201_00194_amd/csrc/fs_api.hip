@@ -324,22 +324,27 @@ extern "C" int64_t fs_colblock64_floats(int64_t n_rows, int32_t n_features)
 
 // ---- scoring -----------------------------------------------------------------------------------
 // Tile groups one workgroup of the LDS traversal takes in a row.  From the second group on, a
-// group's tiles are fetched while the one before it is still being walked, which hides the
-// latency of that fetch; the price is a coarser tail at the end of the launch, so a workgroup
-// only takes several groups while the launch still has some 48 rounds of workgroups per compute
-// unit (measured: 4 groups at 50 rounds -2 %, at 12 rounds +2 %).
+// group's tiles are fetched while the one before it is still being walked, which hides about
+// 1 us of fetch latency per group; the price is a coarser tail at the end of the launch, half a
+// workgroup's time on average.  With R rounds of groups per compute unit and t us per group,
+// G groups per workgroup save R (1 - 1/G) us and cost G t / 2 us: best at G = sqrt(2 R / t).
+// Measured (traversal of configs[3] at full / half / quarter size, configs[4], the foresee
+// step; best G and what it gains): 4 (-3.3 %), 4-6 (-1.6 %), 2-3 (-0.7 %), 1 (any G > 1 loses,
+// 51 us per group), 6 (-2.6 %; 4: -1.8 %).
 constexpr int kLdsMaxGroupsPerWg = 4;
-constexpr int64_t kLdsRoundsPerGroupStep = 48;
 
-static int lds_groups_wanted(int64_t groups_in_launch, int n_compute_units)
+static int lds_groups_wanted(int64_t groups_in_launch, double group_us, int n_compute_units)
 {
     const int forced = tune(FS_TUNE_LDS_GROUPS);
     if (forced >= 1)
         return forced > 16 ? 16 : forced;
-    int64_t g = groups_in_launch / (kLdsRoundsPerGroupStep * (int64_t)n_compute_units);
+    if (groups_in_launch <= 0 || group_us <= 0.0)
+        return 1;
+    const double rounds = (double)groups_in_launch / (double)n_compute_units;
+    int g = (int)sqrt(2.0 * rounds / group_us);
     if (g < 1) g = 1;
     if (g > kLdsMaxGroupsPerWg) g = kLdsMaxGroupsPerWg;
-    return (int)g;
+    return g;
 }
 
 // Row-major input needs no pass of its own where the first kernel to touch the features can
@@ -471,14 +476,23 @@ extern "C" int fs_score_families(int32_t n_families, const fs_family *fams, void
     // tile groups the LDS kernel will see, per workgroup shape (row-major families included:
     // they count towards the length of the launch, though their workgroups take one group each)
     int64_t lds_groups[kLdsModes] = {0, 0};
+    double lds_us[kLdsModes] = {0.0, 0.0};           // all groups of the launch, by the planner's estimate
     for (int f = 0; f < n_families; ++f) {
         const fs_model *m = fams[f].model;
-        if (!m->rank_ok && m->lds_ok)
-            lds_groups[m->lds_mode] += ((fams[f].n_rows + 63) / 64 + m->lds_tiles - 1) / m->lds_tiles;
+        if (!m->rank_ok && m->lds_ok) {
+            const int64_t g = ((fams[f].n_rows + 63) / 64 + m->lds_tiles - 1) / m->lds_tiles;
+            lds_groups[m->lds_mode] += g;
+            lds_us[m->lds_mode] += (double)g * (double)m->lds_group_us;
+        }
     }
     int groups_per_wg[kLdsModes];
-    for (int md = 0; md < kLdsModes; ++md)
-        groups_per_wg[md] = lds_groups_wanted(lds_groups[md], ctx->n_compute_units);
+    for (int md = 0; md < kLdsModes; ++md) {
+        const double group_us = lds_groups[md] ? lds_us[md] / (double)lds_groups[md] : 0.0;
+        groups_per_wg[md] = lds_groups_wanted(lds_groups[md], group_us, ctx->n_compute_units);
+        if (tune(FS_TUNE_VERBOSE) > 0 && lds_groups[md] > 0)
+            fprintf(stderr, "fs_score_families: %lld tile groups of about %.1f us, LDS shape %d: %d per workgroup\n",
+                    (long long)lds_groups[md], group_us, md, groups_per_wg[md]);
+    }
     size_t scratch_pos = 0;
     for (int f = 0; f < n_families; ++f) {
         const fs_family &a = fams[f];

@@ -102,6 +102,7 @@ struct fs_model {
     int32_t lds_mode;      // workgroup shape chosen for this model (index into kLdsMode*)
     int32_t lds_tiles;     // 64-row tiles per workgroup chosen for this model
     int32_t lds_tile0;     // LDS byte offset of the first feature tile
+    float lds_group_us;    // the planner's estimate of one tile group's time in the LDS kernel
     int32_t n_chunks;
     uint8_t *d_image;      // all chunk images back to back
     fs::ChunkHdr *d_chunks;

@@ -642,6 +642,8 @@ extern "C" int fs_model_create(fs_model **out, int32_t n_features, int32_t n_tre
                     });
                     SlotPlan sp;
                     deal_trees(by_depth, tdepth.data() + t, share, &sp);
+                    // (the plan's cost is in units of about 1.5 us: configs[3] 12.1 for 18 us a group)
+                    m->lds_group_us += 1.5f * (float)sp.cost;
                     // records: one per slot first (its first run, or an empty one), then the rest
                     std::vector<int> rec_of(sp.runs.size(), -1);     // record index of every run
                     int n_rec = kLdsMaxWaves;
