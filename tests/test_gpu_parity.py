@@ -571,14 +571,16 @@ def test_maximum_sizes_of_the_interface(api, oracle):
         api.fs_model.from_arrays(big.model)
 
 
-@pytest.mark.parametrize("seed", range(16))
-def test_random_shapes_across_the_kernel_choices(api, oracle, seed):
+@pytest.mark.parametrize("seed", range(48))
+def test_random_shapes_across_the_kernel_choices(api, oracle, tune, seed):
     """Seeded random families: feature counts on both sides of the LDS formats' limit, depths
     0..12 perfect or irregular (so the compact, 8-byte-node, rank-coded and global-memory
     kernels all get picked somewhere), ragged program lengths, both layouts; everything the
     library returns is compared, three families per submission."""
     import torch
     rng = np.random.default_rng([seed, 31337])
+    if seed >= 16:                # the later seeds also force several tile groups per workgroup
+        tune(api.FS_TUNE_LDS_GROUPS, int(rng.choice([2, 3, 4, 16])))
     fams = []
     for i in range(3):
         depth = int(rng.integers(0, 13))

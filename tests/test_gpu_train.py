@@ -161,9 +161,13 @@ def test_errors(api):
     assert tr.size()[0] == 2
 
 
-@pytest.mark.parametrize("seed", range(10))
-def test_random_training_shapes_and_parameters(api, T, seed):
+@pytest.mark.parametrize("seed", range(30))
+def test_random_training_shapes_and_parameters(api, T, tune, seed):
     rng = np.random.default_rng([seed, 777])
+    if seed >= 10:                # the later seeds also vary the histogram form and the row slabs
+        tune(api.FS_TUNE_TRAIN_SLAB_ROWS, int(rng.choice([-1, 512, 3000])))
+        tune(api.FS_TUNE_TRAIN_PACKED, int(rng.choice([-1, 0])))
+        tune(api.FS_TUNE_TRAIN_SORT, int(rng.choice([-1, 0, 1])))
     nf = int(rng.choice([1, 2, 3, 5, 17, 33, 64]))
     ts = W.make_train_set(100 + seed, int(rng.integers(2, 1500)), stmts=(1, int(rng.integers(1, 30))),
                           n_features=nf, max_cuts=int(rng.choice([1, 2, 7, 64, 255])),
